@@ -1,0 +1,196 @@
+"""Oracle: block-mask compaction, work items, greedy (longest-first) partitioning, rho_s.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).
+
+What is followed:
+  * cost of a unit of work = its number of dense mask blocks (Background, "Block-wise
+    Sparse Attention": the dense-block count is the workload);
+  * sparse imbalance ratio rho_s (Motivation, Eq. 1; one-period form: Eq. 2; ring form:
+    Eq. 3);
+  * greedy head-level partitioning (Methodology, "Head-level Partitioning" and the first
+    loop of Alg. 1): sort units by dense-block count, descending; hand each to the
+    partition whose accumulated count is currently smallest.
+
+The paper balances heads over GPUs.  Here the same greedy rule balances finer units --
+(head, query block, range of that row's active KV blocks) -- over P partitions (the
+persistent workgroups of one GPU).  Steps are taken in the paper's order; plain Python
+integers throughout, so results are exact.
+
+Readings where the paper is silent or garbled (all integer rules):
+  * the descending sort is stable: equal weights keep ascending item id;
+  * argmin ties go to the lowest partition index;
+  * Alg. 1's loop header "in enumerate(sorted ids)" is read as "over the sorted ids";
+  * "sum_per_gpu.update()" is read as load[g] += weight of the unit just placed;
+  * partitions have no capacity limit (the published text states none);
+  * rho_s of zero total work is 1.0;
+  * rho_s is always computed from pure block counts, even when a per-item overhead
+    steers the greedy placement.
+"""
+
+from __future__ import annotations
+
+import heapq
+
+import numpy as np
+
+MODE_BALANCED = 0
+MODE_NAIVE = 1
+
+
+def row_counts(mask):
+    """cnt[h*nQ+I] = number of active KV blocks of row (h, I); per-head sums; total.
+
+    `blocks_per_head` is Alg. 1's get_blocks_per_head.
+    """
+    active = np.asarray(mask) != 0
+    cnt = active.sum(axis=2, dtype=np.int64)          # [H, nQ]
+    per_head = [int(x) for x in cnt.sum(axis=1)]
+    flat = [int(x) for x in cnt.reshape(-1)]
+    return flat, per_head, sum(per_head)
+
+
+def compact(mask):
+    """CSR over rows r = h*nQ + I: ascending active KV block ids per row."""
+    mask = np.asarray(mask)
+    H, nQ, nK = mask.shape
+    row_ptr = [0]
+    kv_idx = []
+    for h in range(H):
+        for I in range(nQ):
+            kv_idx.extend(int(J) for J in np.flatnonzero(mask[h, I] != 0))   # ascending J
+            row_ptr.append(len(kv_idx))
+    return row_ptr, kv_idx
+
+
+def auto_max_item_len(total_blocks: int, P: int) -> int:
+    """Split threshold when the caller gives none: max(4, total // (4 P)).
+
+    With every item at most a quarter of the mean partition load, list scheduling's
+    bound (max load <= mean + largest item) keeps rho_s <= 1.25 in the worst case.
+    """
+    return max(4, total_blocks // (4 * P))
+
+
+def make_items(cnt, nQ: int, max_len: int):
+    """Work items in row-major order.
+
+    An item is (head, q_block, kv_begin, kv_end): positions [kv_begin, kv_end) inside the
+    row's compacted list.  Empty rows give no item.  max_len < 0: never split.  A row with
+    cnt > max_len is cut into k = ceil(cnt / max_len) consecutive chunks, chunk t having
+    cnt // k + (1 if t < cnt % k else 0) blocks.
+
+    Also returns, per item, `slot` (-1 for a whole row, else the index of the chunk among
+    all chunks of split rows, in generation order) and the list of split rows as
+    (row, first_slot, n_chunks).
+    """
+    items, slot, split_rows = [], [], []
+    n_slots = 0
+    for r, c in enumerate(cnt):
+        if c == 0:
+            continue
+        h, I = divmod(r, nQ)
+        if max_len < 0 or c <= max_len:
+            items.append((h, I, 0, c))
+            slot.append(-1)
+            continue
+        k = -(-c // max_len)
+        base, extra = divmod(c, k)
+        split_rows.append((r, n_slots, k))
+        pos = 0
+        for t in range(k):
+            ln = base + (1 if t < extra else 0)
+            items.append((h, I, pos, pos + ln))
+            slot.append(n_slots)
+            n_slots += 1
+            pos += ln
+        assert pos == c
+    return items, slot, split_rows
+
+
+def lpt_partition(weights, P: int):
+    """Greedy of Alg. 1 (first loop): returns (assignment per item, load per partition)."""
+    order = sorted(range(len(weights)), key=lambda i: -weights[i])   # Python's sort is stable
+    heap = [(0, g) for g in range(P)]                                # (load, index): lowest index wins ties
+    heapq.heapify(heap)
+    assign = [0] * len(weights)
+    for i in order:
+        load, g = heapq.heappop(heap)
+        assign[i] = g
+        heapq.heappush(heap, (load + weights[i], g))
+    loads = [0] * P
+    for i, g in enumerate(assign):
+        loads[g] += weights[i]
+    return assign, loads
+
+
+def naive_partition(n_items: int, P: int):
+    """Items in generation order, dealt in contiguous runs of ceil(n_items / P)."""
+    if n_items == 0:
+        return []
+    run = -(-n_items // P)
+    return [i // run for i in range(n_items)]
+
+
+def imbalance_ratio(work):
+    """Eq. 1: sum_i max_g b[i][g] / (sum_{i,g} b[i][g] / |G|); work is [periods][partitions]."""
+    work = [[int(x) for x in row] for row in work]
+    G = len(work[0])
+    total = sum(sum(row) for row in work)
+    if total == 0:
+        return 1.0
+    num = sum(max(row) for row in work)
+    return float(num) / (float(total) / float(G))
+
+
+def ring_work_matrix(chunk_blocks):
+    """Eq. 3's b[i][g]: dense blocks between Q chunk g and KV chunk (i+g) mod |G|.
+
+    chunk_blocks[q][kv] = dense blocks (summed over heads) between Q chunk q and KV chunk kv.
+    """
+    G = len(chunk_blocks)
+    return [[int(chunk_blocks[g][(i + g) % G]) for g in range(G)] for i in range(G)]
+
+
+def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0):
+    """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly)."""
+    mask = np.asarray(mask)
+    H, nQ, nK = mask.shape
+    cnt, per_head, total = row_counts(mask)
+    row_ptr, kv_idx = compact(mask)
+    L = auto_max_item_len(total, P) if max_item_len == 0 else max_item_len
+    items, slot, split_rows = make_items(cnt, nQ, L)
+    lens = [e - b for (_, _, b, e) in items]
+    weights = [ln + item_overhead for ln in lens]
+
+    lpt_assign, _ = lpt_partition(weights, P)
+    nv_assign = naive_partition(len(items), P)
+
+    def loads_of(assign):
+        ld = [0] * P
+        for i, g in enumerate(assign):
+            ld[g] += lens[i]
+        return ld
+
+    rho_bal = imbalance_ratio([loads_of(lpt_assign)])
+    rho_naive = imbalance_ratio([loads_of(nv_assign)])
+    assign = lpt_assign if mode == MODE_BALANCED else nv_assign
+
+    # per-partition lists, each in ascending item id = ascending (head, q_block, kv_begin)
+    lists = [[] for _ in range(P)]
+    for i, g in enumerate(assign):
+        lists[g].append(i)
+    part_ptr = [0]
+    part_items = []
+    for g in range(P):
+        part_items.extend(lists[g])
+        part_ptr.append(len(part_items))
+
+    return dict(
+        H=H, nQ=nQ, nK=nK, P=P, max_item_len=L,
+        cnt=cnt, blocks_per_head=per_head, nnz=total,
+        row_ptr=row_ptr, kv_idx=kv_idx,
+        items=items, item_slot=slot, split_rows=split_rows,
+        part_ptr=part_ptr, part_items=part_items,
+        part_load=loads_of(assign),
+        rho_naive=rho_naive, rho_balanced=rho_bal,
+    )
