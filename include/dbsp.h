@@ -1,0 +1,146 @@
+/*
+ * dbsp.h -- C ABI of libdbsp: balanced block-sparse attention forward on one AMD MI355X.
+ *
+ * The library carries the workload-balancing idea of db-SP (arXiv 2511.23113) from "GPUs of
+ * a sequence-parallel group" onto "compute units of one GPU":
+ *   - the cost of a piece of attention work is its number of dense mask blocks
+ *     (paper: Background, "Block-wise Sparse Attention");
+ *   - the sparse imbalance ratio rho_s = (sum over sync periods of the max per-partition
+ *     block count) / (total block count / number of partitions) (paper: Motivation, Eq. 1;
+ *     one-period form Eq. 2);
+ *   - work is balanced with the greedy rule of Alg. 1 / "Head-level Partitioning": sort
+ *     units by block count, descending, and give each to the least-loaded partition.
+ * Attention itself is O = softmax(Q K^T / sqrt(d)) V per head (paper: Background, "Visual
+ * Generative Models"), evaluated only on the dense blocks of a per-head block mask.
+ *
+ * Conventions for every function:
+ *   - returns DBSP_OK (0) on success, a negative dbsp_status on error; never throws;
+ *     dbsp_last_error() gives a thread-local message for the last error on this thread;
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory on
+ *     the current device; the library never takes ownership of caller memory;
+ *   - calls on distinct plans are thread-safe; calls that use the same plan must not
+ *     overlap (a plan owns scratch buffers that a forward call writes).
+ */
+#ifndef DBSP_H
+#define DBSP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dbsp_status {
+  DBSP_OK = 0,
+  DBSP_EINVAL = -1, /* null pointer, non-positive size, unsupported head dim / block size, bad option */
+  DBSP_ESHAPE = -2, /* sequence length not a multiple of the block size, or shapes disagree with the plan */
+  DBSP_ENOMEM = -3, /* host or device allocation failed */
+  DBSP_EHIP = -4    /* a HIP runtime call failed; dbsp_last_error() holds its message */
+} dbsp_status;
+
+/* Opaque, library-owned plan.  Immutable after creation except for its scratch buffers. */
+typedef struct dbsp_plan dbsp_plan;
+
+enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1 };
+enum { DBSP_PLAN_HOST_ONLY = 1 }; /* flags bit: build the plan on the host only (no device, no upload);
+                                     such a plan cannot be passed to sparse_attn_fwd */
+
+typedef struct dbsp_plan_opts {
+  int32_t num_partitions; /* P >= 1; 0 -> number of compute units of the current device (256 when no device) */
+  int32_t mode;           /* DBSP_MODE_BALANCED: greedy longest-first placement (Alg. 1, first loop);
+                             DBSP_MODE_NAIVE: items in row-major order dealt in contiguous runs of
+                             ceil(n_items / P) -- the unbalanced baseline rho_s is quoted against */
+  int32_t max_item_len;   /* split threshold in blocks: a row with more active blocks is cut into
+                             ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (4 P)); < 0 -> never split */
+  int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
+                             (rho_s is always computed from pure block counts). 0 = the paper's cost model */
+  int32_t flags;          /* DBSP_PLAN_HOST_ONLY or 0 */
+} dbsp_plan_opts;
+
+/*
+ * plan_sparse_attn -- compact a block mask and build the (balanced) work list.
+ *
+ * mask_host: host, uint8 [H, nQ, nK] row-major; nonzero = the (query block, key block) pair is
+ *            computed (a "dense block").  Read during the call only.
+ * block:     block size b in tokens; the forward pass supports 64 and 128.
+ * opts:      host, may be NULL (all zero = defaults).
+ * out_plan:  receives the plan; free it with dbsp_plan_destroy.
+ *
+ * Steps (all integer): per-row counts and per-head sums (Alg. 1, get_blocks_per_head); ascending
+ * KV-block index list per row; work items (head, q_block, kv_begin, kv_end) in row-major order
+ * with long rows split; greedy placement: stable sort by weight descending, each item to the
+ * partition with the smallest accumulated weight (ties: lowest index); each partition's list
+ * in ascending item order; rho_s of the naive and the greedy placement (Eq. 1 with one period).
+ * Unless DBSP_PLAN_HOST_ONLY is set, the arrays are then copied to the current device and
+ * scratch for split rows and busy-time capture is allocated there.
+ * Errors: DBSP_EINVAL, DBSP_ENOMEM, DBSP_EHIP.  Rows with no active block are legal.
+ */
+int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
+                     const dbsp_plan_opts* opts, dbsp_plan** out_plan);
+
+/*
+ * sparse_attn_fwd -- block-sparse attention forward over a plan's work list.
+ *
+ * q:   device, bf16 [B, H, Nq, d] contiguous (d fastest);  k, v: device, bf16 [B, H, Nk, d].
+ * o:   device, bf16 [B, H, Nq, d], written.  lse: device, f32 [B, H, Nq], written; may be NULL.
+ *      LSE = natural log of the sum of exp(softmax_scale * q.k) over the row's active keys.
+ * Nq == nQ * block and Nk == nK * block of the plan (else DBSP_ESHAPE); d in {64, 128};
+ * the mask has no batch axis: every batch entry uses the same per-head mask.
+ * softmax_scale <= 0 selects 1 / sqrt(d).  A query row with no active block gets O = 0, LSE = -inf.
+ * stream: a hipStream_t (NULL = default stream).  The call only enqueues work: one persistent
+ * kernel with one workgroup per partition, plus a small fix-up kernel when rows were split or
+ * are empty.  It does not synchronise with the host.  bf16 inputs, f32 accumulation.
+ * Errors: DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM (scratch growth for B > 1), DBSP_EHIP.
+ */
+int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
+                    float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
+                    void* stream);
+
+/*
+ * imbalance_ratio -- Eq. 1 on a host matrix work[periods][partitions] (row-major, int64, >= 0):
+ * rho = sum_i max_g work[i][g] / (sum_{i,g} work[i][g] / partitions), in double.  Zero total
+ * work gives 1.0.  Errors: DBSP_EINVAL (null pointer, non-positive size, negative entry).
+ */
+int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, double* rho_out);
+
+/* Plan arrays (host copies, owned by the plan, valid until dbsp_plan_destroy). */
+enum dbsp_plan_array {
+  DBSP_ROW_PTR = 0,         /* int32 [H*nQ + 1]  CSR offsets over rows r = h*nQ + I                  */
+  DBSP_KV_IDX = 1,          /* int32 [nnz]       ascending active KV block ids of each row            */
+  DBSP_ITEMS = 2,           /* int32 [n_items*4] (head, q_block, kv_begin, kv_end); begin/end are
+                               positions inside the row's list                                        */
+  DBSP_ITEM_SLOT = 3,       /* int32 [n_items]   -1 = whole row; else index of this chunk among all
+                               chunks of split rows, in item order                                    */
+  DBSP_SPLIT_ROWS = 4,      /* int32 [n_split*4] (row, first_slot, n_chunks, 0)                       */
+  DBSP_PART_PTR = 5,        /* int32 [P + 1]     offsets into PART_ITEMS                              */
+  DBSP_PART_ITEMS = 6,      /* int32 [n_items]   item ids of each partition, ascending                */
+  DBSP_PART_LOAD = 7,       /* int64 [P]         active blocks per partition (pure block counts)      */
+  DBSP_BLOCKS_PER_HEAD = 8, /* int64 [H]         active blocks per head                               */
+  DBSP_ROW_CNT = 9,         /* int32 [H*nQ]      active blocks per row                                */
+  DBSP_EMPTY_ROWS = 10      /* int32 [n_empty]   rows with no active block                            */
+};
+
+/* dbsp_plan_get: *data points to the array, *count is its number of ELEMENTS of the type above. */
+int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_t* count);
+
+/* dbsp_plan_stats: any output pointer may be NULL.  rho_* are Eq. 1 (one period) on pure block
+ * counts for the naive and the greedy placement of the SAME item list; plan_usec is the host
+ * time spent inside plan_sparse_attn (including the device upload). */
+int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, int64_t* nnz,
+                    int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
+                    double* plan_usec);
+
+/* dbsp_plan_busy: per-partition busy time of the LAST sparse_attn_fwd on this plan.
+ * busy_ticks: host, uint64 [P], ticks of the 100 MHz constant clock summed over the partition's
+ * items; hw_id: host, uint32 [P], (XCC id << 16) | (SE id << 8) | CU id the workgroup ran on;
+ * either may be NULL.  Synchronises `stream` before reading. */
+int dbsp_plan_busy(const dbsp_plan* plan, uint64_t* busy_ticks, uint32_t* hw_id, void* stream);
+
+void dbsp_plan_destroy(dbsp_plan* plan);
+
+const char* dbsp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBSP_H */

@@ -1,0 +1,16 @@
+"""MI355X-native balanced block-sparse attention (the single-GPU hot path of db-SP, arXiv 2511.23113).
+
+The product is libdbsp.so (HIP for gfx950 + a C++ host planner) behind the C ABI declared in
+include/dbsp.h; this package is its thin Python binding.
+"""
+
+from .binding import (  # noqa: F401
+    DbspError,
+    MODE_BALANCED,
+    MODE_NAIVE,
+    Plan,
+    imbalance_ratio,
+    load_library,
+    plan_sparse_attn,
+    sparse_attn_fwd,
+)

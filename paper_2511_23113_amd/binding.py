@@ -1,0 +1,187 @@
+"""ctypes binding of libdbsp's C ABI (include/dbsp.h): argument marshalling only.
+
+Every step of the hot path runs inside the library; nothing here computes.  The library is
+loaded from this package's directory; if it has not been built yet it is built once with
+hipcc, and any failure to build or load raises -- there is no CPU fallback.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+DBSP_OK, DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM, DBSP_EHIP = 0, -1, -2, -3, -4
+MODE_BALANCED, MODE_NAIVE = 0, 1
+PLAN_HOST_ONLY = 1
+
+ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, BLOCKS_PER_HEAD, ROW_CNT, EMPTY_ROWS = range(11)
+_INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
+
+EXPORTS = (
+    "plan_sparse_attn", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
+    "dbsp_plan_busy", "dbsp_plan_destroy", "dbsp_last_error",
+)
+
+
+class DbspError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libdbsp error {code}: {msg}")
+        self.code = code
+
+
+class PlanOpts(C.Structure):
+    _fields_ = [("num_partitions", C.c_int32), ("mode", C.c_int32), ("max_item_len", C.c_int32),
+                ("item_overhead", C.c_int32), ("flags", C.c_int32)]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None):
+    """Load libdbsp.so (building it first if it does not exist).  Raises if that fails."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build()
+    lib = C.CDLL(path)
+    vp, i32, i64p = C.c_void_p, C.c_int32, C.POINTER(C.c_int64)
+    lib.plan_sparse_attn.argtypes = [vp, i32, i32, i32, i32, C.POINTER(PlanOpts), C.POINTER(vp)]
+    lib.plan_sparse_attn.restype = C.c_int
+    lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
+    lib.sparse_attn_fwd.restype = C.c_int
+    lib.imbalance_ratio.argtypes = [vp, i32, i32, C.POINTER(C.c_double)]
+    lib.imbalance_ratio.restype = C.c_int
+    lib.dbsp_plan_get.argtypes = [vp, i32, C.POINTER(vp), i64p]
+    lib.dbsp_plan_get.restype = C.c_int
+    lib.dbsp_plan_stats.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), i64p, i64p,
+                                    C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+    lib.dbsp_plan_stats.restype = C.c_int
+    lib.dbsp_plan_busy.argtypes = [vp, vp, vp, vp]
+    lib.dbsp_plan_busy.restype = C.c_int
+    lib.dbsp_plan_destroy.argtypes = [vp]
+    lib.dbsp_plan_destroy.restype = None
+    lib.dbsp_last_error.argtypes = []
+    lib.dbsp_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != DBSP_OK:
+        raise DbspError(rc, load_library().dbsp_last_error().decode("utf-8", "replace"))
+
+
+class Plan:
+    """Owner of a dbsp_plan*; destroyed on close() or garbage collection."""
+
+    def __init__(self, handle: int, H: int, nQ: int, nK: int, block: int):
+        self._h = C.c_void_p(handle)
+        self.H, self.nQ, self.nK, self.block = H, nQ, nK, block
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("plan already destroyed")
+        return self._h
+
+    def array(self, what: int) -> np.ndarray:
+        """Copy of one plan array (see dbsp_plan_array in dbsp.h)."""
+        data, count = C.c_void_p(), C.c_int64()
+        _check(load_library().dbsp_plan_get(self.handle, what, C.byref(data), C.byref(count)))
+        dt = np.int64 if what in _INT64_ARRAYS else np.int32
+        if count.value == 0:
+            return np.zeros(0, dtype=dt)
+        ctype = C.c_int64 if dt is np.int64 else C.c_int32
+        buf = C.cast(data, C.POINTER(ctype * count.value)).contents
+        return np.frombuffer(buf, dtype=dt).copy()
+
+    def stats(self) -> dict:
+        rn, rb, pu = C.c_double(), C.c_double(), C.c_double()
+        nnz, ni = C.c_int64(), C.c_int64()
+        P, L = C.c_int32(), C.c_int32()
+        _check(load_library().dbsp_plan_stats(self.handle, C.byref(rn), C.byref(rb), C.byref(nnz), C.byref(ni),
+                                              C.byref(P), C.byref(L), C.byref(pu)))
+        return dict(rho_naive=rn.value, rho_balanced=rb.value, nnz=nnz.value, n_items=ni.value,
+                    num_partitions=P.value, max_item_len=L.value, plan_usec=pu.value)
+
+    def busy(self, stream=None):
+        """(busy ticks uint64 [P] at 100 MHz, hw ids uint32 [P]) of the last forward call; synchronises."""
+        P = self.stats()["num_partitions"]
+        ticks = np.zeros(P, dtype=np.uint64)
+        hw = np.zeros(P, dtype=np.uint32)
+        _check(load_library().dbsp_plan_busy(self.handle, ticks.ctypes.data_as(C.c_void_p),
+                                             hw.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
+        return ticks, hw
+
+    def close(self):
+        if self._h:
+            load_library().dbsp_plan_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
+                     max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False) -> Plan:
+    """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.ndim != 3:
+        raise ValueError("mask must be [H, nQ, nK]")
+    H, nQ, nK = mask.shape
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0)
+    out = C.c_void_p()
+    _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
+    return Plan(out.value, H, nQ, nK, block)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        if torch.cuda.is_available():
+            return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        return C.c_void_p(0)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def sparse_attn_fwd(plan: Plan, q, k, v, o=None, lse=None, softmax_scale: float = 0.0, stream=None, want_lse: bool = True):
+    """q [B,H,Nq,d], k/v [B,H,Nk,d]: contiguous bf16 torch tensors on the GPU.  Enqueues on
+    `stream` (default: torch's current stream) and returns (o, lse) without synchronising."""
+    import torch
+    for name, x in (("q", q), ("k", k), ("v", v)):
+        if x.dtype != torch.bfloat16 or not x.is_cuda or not x.is_contiguous() or x.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d bf16 tensor on the GPU")
+    B, H, Nq, d = q.shape
+    Nk = k.shape[2]
+    if k.shape != (B, H, Nk, d) or v.shape != k.shape or H != plan.H:
+        raise ValueError("q/k/v shapes disagree with each other or with the plan")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((B, H, Nq), dtype=torch.float32, device=q.device)
+    lse_ptr = C.c_void_p(lse.data_ptr()) if lse is not None else C.c_void_p(0)
+    _check(load_library().sparse_attn_fwd(plan.handle, C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+                                          C.c_void_p(v.data_ptr()), C.c_void_p(o.data_ptr()), lse_ptr,
+                                          B, Nq, Nk, d, float(softmax_scale), _stream_ptr(stream)))
+    return o, lse
+
+
+def imbalance_ratio(work) -> float:
+    """Eq. 1 of the paper on an integer matrix work[periods][partitions]."""
+    w = np.ascontiguousarray(work, dtype=np.int64)
+    if w.ndim == 1:
+        w = w[None]
+    rho = C.c_double()
+    _check(load_library().imbalance_ratio(w.ctypes.data_as(C.c_void_p), w.shape[0], w.shape[1], C.byref(rho)))
+    return rho.value

@@ -1,0 +1,175 @@
+// Host planner: block-mask compaction, work items, greedy longest-first placement, rho_s.
+//
+// Cost model and rules come from db-SP (arXiv 2511.23113): the work of a unit is its number of
+// dense mask blocks (Background, "Block-wise Sparse Attention"); rho_s is Eq. 1 (Motivation);
+// placement is the greedy of "Head-level Partitioning" / Alg. 1's first loop, applied to
+// (head, query block, KV range) items and P partitions instead of heads and GPUs.
+// Everything here is integer arithmetic; the only floating point is the final rho_s division.
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "plan.hpp"
+
+namespace {
+
+// Append the ascending indices of the nonzero bytes of row[0..n) to `out`; returns how many.
+inline int32_t compact_row(const uint8_t* row, int32_t n, std::vector<int32_t>& out) {
+  const size_t before = out.size();
+  int32_t j = 0;
+  for (; j + 8 <= n; j += 8) {
+    uint64_t w;
+    std::memcpy(&w, row + j, 8);
+    if (w == 0) continue;
+    for (int32_t t = 0; t < 8; ++t)
+      if (row[j + t]) out.push_back(j + t);
+  }
+  for (; j < n; ++j)
+    if (row[j]) out.push_back(j);
+  return (int32_t)(out.size() - before);
+}
+
+// Binary min-heap over partitions keyed by (load, index): the root is the least-loaded
+// partition, lowest index among equals.  Only the root's key ever grows, so one sift-down
+// per placement is enough.
+struct LoadHeap {
+  std::vector<int64_t> load;
+  std::vector<int32_t> heap;  // partition ids
+  explicit LoadHeap(int32_t P) : load(P, 0), heap(P) {
+    for (int32_t g = 0; g < P; ++g) heap[g] = g;  // all loads equal: ascending ids form a valid heap
+  }
+  bool less(int32_t a, int32_t b) const { return load[a] < load[b] || (load[a] == load[b] && a < b); }
+  int32_t place(int64_t w) {
+    const int32_t g = heap[0];
+    load[g] += w;
+    const size_t n = heap.size();
+    size_t i = 0;
+    for (;;) {
+      size_t l = 2 * i + 1, r = l + 1, m = i;
+      if (l < n && less(heap[l], heap[m])) m = l;
+      if (r < n && less(heap[r], heap[m])) m = r;
+      if (m == i) break;
+      std::swap(heap[i], heap[m]);
+      i = m;
+    }
+    return g;
+  }
+};
+
+}  // namespace
+
+double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions) {
+  int64_t total = 0, num = 0;
+  for (int32_t i = 0; i < periods; ++i) {
+    int64_t mx = 0;
+    for (int32_t g = 0; g < partitions; ++g) {
+      const int64_t w = work[(int64_t)i * partitions + g];
+      total += w;
+      mx = std::max(mx, w);
+    }
+    num += mx;
+  }
+  if (total == 0) return 1.0;
+  return (double)num / ((double)total / (double)partitions);
+}
+
+int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
+                         int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
+                         dbsp_host_plan& hp, std::string& err) {
+  try {
+    const int64_t R = (int64_t)H * nQ;
+    hp.H = H; hp.nQ = nQ; hp.nK = nK; hp.block = block;
+    hp.P = P; hp.mode = mode; hp.item_overhead = item_overhead;
+
+    // counts + compaction in one pass over the mask
+    hp.row_cnt.resize(R);
+    hp.row_ptr.resize(R + 1);
+    hp.blocks_per_head.assign(H, 0);
+    hp.kv_idx.clear();
+    hp.row_ptr[0] = 0;
+    for (int64_t r = 0; r < R; ++r) {
+      const int32_t c = compact_row(mask + r * nK, nK, hp.kv_idx);
+      if (hp.kv_idx.size() > (size_t)INT32_MAX) { err = "more than 2^31-1 active blocks"; return DBSP_EINVAL; }
+      hp.row_cnt[r] = c;
+      hp.row_ptr[r + 1] = (int32_t)hp.kv_idx.size();
+      hp.blocks_per_head[r / nQ] += c;
+    }
+    hp.nnz = (int64_t)hp.kv_idx.size();
+
+    // split threshold
+    int32_t L = max_item_len;
+    if (L == 0) L = (int32_t)std::max<int64_t>(4, hp.nnz / (4 * (int64_t)P));
+    hp.max_item_len = L;
+
+    // items in row-major order
+    hp.items.clear(); hp.item_slot.clear(); hp.split_rows.clear(); hp.empty_rows.clear();
+    hp.n_slots = 0;
+    for (int64_t r = 0; r < R; ++r) {
+      const int32_t c = hp.row_cnt[r];
+      const int32_t h = (int32_t)(r / nQ), I = (int32_t)(r % nQ);
+      if (c == 0) { hp.empty_rows.push_back((int32_t)r); continue; }
+      if (L < 0 || c <= L) {
+        hp.items.insert(hp.items.end(), {h, I, 0, c});
+        hp.item_slot.push_back(-1);
+        continue;
+      }
+      const int32_t k = (c + L - 1) / L, base = c / k, extra = c % k;
+      hp.split_rows.insert(hp.split_rows.end(), {(int32_t)r, hp.n_slots, k, 0});
+      int32_t pos = 0;
+      for (int32_t t = 0; t < k; ++t) {
+        const int32_t len = base + (t < extra ? 1 : 0);
+        hp.items.insert(hp.items.end(), {h, I, pos, pos + len});
+        hp.item_slot.push_back(hp.n_slots++);
+        pos += len;
+      }
+    }
+    const int64_t n_items = hp.n_items();
+
+    // naive placement: contiguous runs of ceil(n_items / P)
+    std::vector<int32_t> assign_naive(n_items), assign_lpt(n_items);
+    const int64_t run = n_items ? (n_items + P - 1) / P : 1;
+    for (int64_t i = 0; i < n_items; ++i) assign_naive[i] = (int32_t)(i / run);
+
+    // greedy placement.  Stable descending order by weight through a counting sort: weights
+    // are bounded by nK + item_overhead, and filling each bucket in ascending id keeps ties stable.
+    {
+      const int64_t wmax = (int64_t)nK + item_overhead;
+      std::vector<int64_t> bucket_start(wmax + 2, 0);
+      auto weight = [&](int64_t i) { return (int64_t)(hp.items[4 * i + 3] - hp.items[4 * i + 2]) + item_overhead; };
+      for (int64_t i = 0; i < n_items; ++i) bucket_start[wmax - weight(i) + 1]++;
+      for (int64_t w = 0; w <= wmax; ++w) bucket_start[w + 1] += bucket_start[w];
+      std::vector<int32_t> order(n_items);
+      for (int64_t i = 0; i < n_items; ++i) order[bucket_start[wmax - weight(i)]++] = (int32_t)i;
+      LoadHeap heap(P);
+      for (int64_t t = 0; t < n_items; ++t) {
+        const int32_t i = order[t];
+        assign_lpt[i] = heap.place(weight(i));
+      }
+    }
+
+    auto loads_of = [&](const std::vector<int32_t>& a) {
+      std::vector<int64_t> ld(P, 0);
+      for (int64_t i = 0; i < n_items; ++i) ld[a[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
+      return ld;
+    };
+    const std::vector<int64_t> ld_naive = loads_of(assign_naive), ld_lpt = loads_of(assign_lpt);
+    hp.rho_naive = dbsp_rho(ld_naive.data(), 1, P);
+    hp.rho_balanced = dbsp_rho(ld_lpt.data(), 1, P);
+
+    const std::vector<int32_t>& assign = (mode == DBSP_MODE_NAIVE) ? assign_naive : assign_lpt;
+    hp.part_load = (mode == DBSP_MODE_NAIVE) ? ld_naive : ld_lpt;
+
+    // per-partition lists in ascending item id (= ascending head, q_block, kv_begin)
+    hp.part_ptr.assign(P + 1, 0);
+    for (int64_t i = 0; i < n_items; ++i) hp.part_ptr[assign[i] + 1]++;
+    for (int32_t g = 0; g < P; ++g) hp.part_ptr[g + 1] += hp.part_ptr[g];
+    hp.part_items.resize(n_items);
+    std::vector<int32_t> cursor(hp.part_ptr.begin(), hp.part_ptr.end() - 1);
+    for (int64_t i = 0; i < n_items; ++i) hp.part_items[cursor[assign[i]]++] = (int32_t)i;
+    return DBSP_OK;
+  } catch (const std::bad_alloc&) {
+    err = "out of host memory while planning";
+    return DBSP_ENOMEM;
+  }
+}

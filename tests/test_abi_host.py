@@ -1,0 +1,149 @@
+"""Host-side checks of libdbsp through its C ABI (no GPU needed): the library loads and
+exports every symbol dbsp.h declares, argument errors map to the documented codes, and the
+planner's integer arrays and rho_s equal the oracle's bit for bit."""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import planner as op
+from paper_2511_23113_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    header = open(os.path.join(ROOT, "include", "dbsp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(?:int|void|const char\s*\*)\s+([a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def _plan_raw(mask_ptr, H, nQ, nK, block, opts=None):
+    lib = B.load_library()
+    out = C.c_void_p()
+    rc = lib.plan_sparse_attn(mask_ptr, H, nQ, nK, block, C.byref(opts) if opts is not None else None, C.byref(out))
+    return rc, out
+
+
+def test_argument_errors():
+    lib = B.load_library()
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    mp = m.ctypes.data_as(C.c_void_p)
+    host = B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY)
+    assert _plan_raw(None, 1, 2, 2, 64, host)[0] == B.DBSP_EINVAL
+    assert lib.plan_sparse_attn(mp, 1, 2, 2, 64, C.byref(host), None) == B.DBSP_EINVAL
+    for bad in ((0, 2, 2, 64), (1, 0, 2, 64), (1, 2, -1, 64), (1, 2, 2, 0)):
+        assert _plan_raw(mp, *bad, host)[0] == B.DBSP_EINVAL
+    assert b"positive" in lib.dbsp_last_error()
+    assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(-1, 0, 0, 0, B.PLAN_HOST_ONLY))[0] == B.DBSP_EINVAL
+    assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(4, 7, 0, 0, B.PLAN_HOST_ONLY))[0] == B.DBSP_EINVAL
+    assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(4, 0, 0, -2, B.PLAN_HOST_ONLY))[0] == B.DBSP_EINVAL
+    assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(4, 0, 0, 0, 8))[0] == B.DBSP_EINVAL
+    rc, plan = _plan_raw(mp, 1, 2, 2, 64, host)
+    assert rc == B.DBSP_OK and plan.value
+    one = C.c_void_p(16)  # never dereferenced: every call below must fail on its checks first
+    fwd = lambda *a: lib.sparse_attn_fwd(*a)
+    assert fwd(None, one, one, one, one, None, 1, 128, 128, 64, 0.0, None) == B.DBSP_EINVAL
+    assert fwd(plan, None, one, one, one, None, 1, 128, 128, 64, 0.0, None) == B.DBSP_EINVAL
+    assert fwd(plan, one, one, one, one, None, 0, 128, 128, 64, 0.0, None) == B.DBSP_EINVAL
+    assert fwd(plan, one, one, one, one, None, 1, 128, 128, 96, 0.0, None) == B.DBSP_EINVAL
+    assert fwd(plan, one, one, one, one, None, 1, 130, 128, 64, 0.0, None) == B.DBSP_ESHAPE
+    assert fwd(plan, one, one, one, one, None, 1, 128, 256, 64, 0.0, None) == B.DBSP_ESHAPE
+    assert fwd(plan, one, one, one, one, None, 1, 128, 128, 64, 0.0, None) == B.DBSP_EINVAL  # host-only plan
+    assert b"host-only" in lib.dbsp_last_error()
+    assert lib.dbsp_plan_busy(plan, None, None, None) == B.DBSP_EINVAL
+    data, cnt = C.c_void_p(), C.c_int64()
+    assert lib.dbsp_plan_get(plan, 99, C.byref(data), C.byref(cnt)) == B.DBSP_EINVAL
+    assert lib.dbsp_plan_get(plan, B.ROW_PTR, None, C.byref(cnt)) == B.DBSP_EINVAL
+    lib.dbsp_plan_destroy(plan)
+    lib.dbsp_plan_destroy(None)
+    # unsupported block size is a forward-pass error, not a planning error
+    rc, plan = _plan_raw(mp, 1, 2, 2, 32, host)
+    assert rc == B.DBSP_OK
+    assert fwd(plan, one, one, one, one, None, 1, 64, 64, 64, 0.0, None) == B.DBSP_EINVAL
+    lib.dbsp_plan_destroy(plan)
+    rho = C.c_double()
+    w = np.array([[1, 2]], dtype=np.int64)
+    assert lib.imbalance_ratio(None, 1, 2, C.byref(rho)) == B.DBSP_EINVAL
+    assert lib.imbalance_ratio(w.ctypes.data_as(C.c_void_p), 0, 2, C.byref(rho)) == B.DBSP_EINVAL
+    wn = np.array([[1, -2]], dtype=np.int64)
+    assert lib.imbalance_ratio(wn.ctypes.data_as(C.c_void_p), 1, 2, C.byref(rho)) == B.DBSP_EINVAL
+
+
+def test_imbalance_ratio_matches_oracle_and_hand_values():
+    assert B.imbalance_ratio([[12, 4]]) == 1.5
+    assert B.imbalance_ratio([[4, 3], [0, 1]]) == 1.25
+    assert B.imbalance_ratio([[0, 0, 0]]) == 1.0
+    rng = np.random.default_rng(5)
+    for _ in range(100):
+        w = rng.integers(0, 1000, size=(int(rng.integers(1, 6)), int(rng.integers(1, 20))))
+        assert B.imbalance_ratio(w) == op.imbalance_ratio(w.tolist())
+
+
+def _assert_plan_equal(mask, block, P, mode, L, c0):
+    pl = B.plan_sparse_attn(mask, block, num_partitions=P, mode=mode, max_item_len=L, item_overhead=c0, host_only=True)
+    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0)
+    st = pl.stats()
+    assert st["nnz"] == ref["nnz"] and st["n_items"] == len(ref["items"])
+    assert st["num_partitions"] == P and st["max_item_len"] == ref["max_item_len"]
+    assert st["rho_naive"] == ref["rho_naive"] and st["rho_balanced"] == ref["rho_balanced"]   # bit-exact doubles
+    eq = np.testing.assert_array_equal
+    eq(pl.array(B.ROW_CNT), np.array(ref["cnt"], dtype=np.int32))
+    eq(pl.array(B.BLOCKS_PER_HEAD), np.array(ref["blocks_per_head"], dtype=np.int64))
+    eq(pl.array(B.ROW_PTR), np.array(ref["row_ptr"], dtype=np.int32))
+    eq(pl.array(B.KV_IDX), np.array(ref["kv_idx"], dtype=np.int32))
+    eq(pl.array(B.ITEMS), np.array(ref["items"], dtype=np.int32).reshape(-1))
+    eq(pl.array(B.ITEM_SLOT), np.array(ref["item_slot"], dtype=np.int32))
+    eq(pl.array(B.SPLIT_ROWS), np.array([(r, s, k, 0) for r, s, k in ref["split_rows"]], dtype=np.int32).reshape(-1))
+    eq(pl.array(B.PART_PTR), np.array(ref["part_ptr"], dtype=np.int32))
+    eq(pl.array(B.PART_ITEMS), np.array(ref["part_items"], dtype=np.int32))
+    eq(pl.array(B.PART_LOAD), np.array(ref["part_load"], dtype=np.int64))
+    empty = [r for r, c in enumerate(ref["cnt"]) if c == 0]
+    eq(pl.array(B.EMPTY_ROWS), np.array(empty, dtype=np.int32))
+    pl.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_planner_bit_exact_on_configs(cfg):
+    mask = synth.mask_for_config(cfg)
+    block = synth.CONFIGS[cfg]["block"]
+    for mode in (B.MODE_BALANCED, B.MODE_NAIVE):
+        _assert_plan_equal(mask, block, 256, mode, 0, 0)
+    if cfg in (1, 5):
+        _assert_plan_equal(mask, block, 8, B.MODE_BALANCED, 0, 0)
+        _assert_plan_equal(mask, block, 304, B.MODE_BALANCED, 16, 3)
+        _assert_plan_equal(mask, block, 256, B.MODE_BALANCED, -1, 0)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_planner_bit_exact_random_small(seed):
+    rng = np.random.default_rng(100 + seed)
+    H, nQ, nK = int(rng.integers(1, 5)), int(rng.integers(1, 20)), int(rng.integers(1, 40))
+    mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0.0, 1.0)), seed=seed)
+    if seed % 4 == 0:
+        mask[0, 0, :] = 0                      # an empty row
+    for P in (1, 2, 5, 300):
+        for mode in (B.MODE_BALANCED, B.MODE_NAIVE):
+            for L, c0 in ((0, 0), (-1, 0), (3, 0), (0, 2)):
+                _assert_plan_equal(mask, 64, P, mode, L, c0)
+
+
+def test_planner_degenerate_masks():
+    _assert_plan_equal(np.zeros((2, 3, 5), dtype=np.uint8), 64, 4, B.MODE_BALANCED, 0, 0)
+    _assert_plan_equal(np.ones((2, 3, 5), dtype=np.uint8), 64, 4, B.MODE_BALANCED, 0, 0)
+    _assert_plan_equal(np.ones((1, 1, 9), dtype=np.uint8), 64, 4, B.MODE_NAIVE, 2, 0)
+    _assert_plan_equal(np.full((1, 2, 17), 255, dtype=np.uint8), 128, 1, B.MODE_BALANCED, 0, 0)   # any nonzero byte counts
+
+
+def test_five_config5_steps_replan_bit_exact():
+    # per-call replanning over the denoising-step sequence (first steps only, to stay quick)
+    for step, mask in enumerate(synth.mask_sequence_cfg5(4)):
+        _assert_plan_equal(mask, 128, 256, B.MODE_BALANCED, 0, 0)
