@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse attention hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: plan_sparse_attn
+(mask compaction, work items, greedy placement, rho_s, plan upload) followed by
+sparse_attn_fwd (persistent kernel + fix-up).  Q/K/V live in HBM before the timed region; the
+block mask is a host array, as the C ABI takes it.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
+
+
+def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
+    """The oracle as it stands, timed on this host on a bounded, seeded sample of rows."""
+    import numpy as np
+    import synth
+    from oracle import attention as oa
+    block, d = c["block"], c["d"]
+    rng = np.random.default_rng(12345)
+    H, nQ, _ = mask.shape
+    order = [(0, int(h), int(I)) for h in range(H) for I in rng.choice(nQ, size=min(nQ, 4), replace=False)]
+    rng.shuffle(order)
+    cnt = (mask != 0).sum(2)
+    heads = {}
+    def head_f32(h):
+        if h not in heads:
+            heads.clear()
+            heads[h] = tuple(synth.bf16_bits_to_f32(x[:, h:h + 1]) for x in (qb, kb, vb))
+        return heads[h]
+    t_used, blocks, rows = 0.0, 0, 0
+    for (b, h, I) in order:
+        q32, k32, v32 = head_f32(h)
+        t0 = time.perf_counter()
+        oa.masked_attention_rows(q32, k32, v32, mask[h:h + 1], block, [(0, 0, I)])
+        t_used += time.perf_counter() - t0
+        blocks += int(cnt[h, I])
+        rows += 1
+        if t_used >= budget_s:
+            break
+    tflops = blocks * 4.0 * block * block * d / t_used / 1e12
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": tflops, "unit": "TFLOP/s (active blocks)", "cores": min(threads, os.cpu_count() or threads),
+            "kind": "oracle", "host_cpus": os.cpu_count(),
+            "sample": f"{rows} seeded (head, q-block) rows of the same workload, {blocks} active blocks, "
+                      f"{t_used:.1f} s of float64 numpy; throughput extrapolated by active-block count"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload config (3 = Wan-14B-like 480p, the headline shape)")
+    ap.add_argument("--partitions", type=int, default=0, help="0 = one per compute unit")
+    ap.add_argument("--reuse-plan", action="store_true", help="static-mask mode: plan once outside the timed region")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (one GPU's share of the workload "
+              "at its real shape is what is measured).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2511_23113_amd as dbsp
+    import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = args.config
+    c = synth.config_shape(cfg)
+    block, d, B = c["block"], c["d"], c["B"]
+    mask = synth.mask_for_config(cfg)
+    qb, kb, vb = synth.qkv_for_config(cfg, B, c["H"], c["Nq"], c["Nk"], d)
+    dev = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    q, k, v = dev(qb), dev(kb), dev(vb)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, c["H"], c["Nq"]), dtype=torch.float32, device="cuda")
+    nnz = int((mask != 0).sum())
+    flops = float(B) * nnz * 4.0 * block * block * d
+
+    def one_plan(mode):
+        return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode)
+
+    def measured_rho(plan):
+        ticks, hw = plan.busy()
+        percu = {}
+        for tk, idv in zip(ticks.tolist(), hw.tolist()):
+            percu[idv] = percu.get(idv, 0) + tk
+        vals = np.array(list(percu.values()), dtype=np.float64)
+        return float(vals.max() / vals.mean()) if vals.sum() > 0 else 1.0, len(percu)
+
+    # side measurement (untimed region): naive vs balanced placement, kernel only
+    side = {}
+    for name, mode in (("naive", dbsp.MODE_NAIVE), ("balanced", dbsp.MODE_BALANCED)):
+        plan = one_plan(mode)
+        for _ in range(2):
+            dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+        e1.record()
+        torch.cuda.synchronize()
+        rho_meas, n_cu = measured_rho(plan)
+        st = plan.stats()
+        side[name] = dict(kernel_ms=e0.elapsed_time(e1) / 3, rho_blocks=st["rho_" + name], rho_busy_per_cu=rho_meas, cus_seen=n_cu)
+        plan.close()
+
+    # timed region: K steps of plan + forward
+    plans = []
+    static_plan = one_plan(dbsp.MODE_BALANCED) if args.reuse_plan else None
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    plan_us = []
+
+    def step(i, timed):
+        plan = static_plan if static_plan is not None else one_plan(dbsp.MODE_BALANCED)
+        if timed:
+            ev[i][0].record()
+        dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+        if timed:
+            ev[i][1].record()
+            plan_us.append(plan.stats()["plan_usec"])
+        if static_plan is None:
+            plans.append(plan)
+            if len(plans) > 2:          # released two steps later (freeing device memory waits for the device)
+                plans.pop(0).close()
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    total_s = t1 - t0
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    kern_avg = float(np.mean(kern_ms))
+    for p in plans:
+        p.close()
+    if static_plan is not None:
+        static_plan.close()
+
+    value = flops * args.steps / total_s / 1e12
+    kern_tflops = flops / (kern_avg * 1e-3) / 1e12
+    out = {
+        "metric": "block-sparse attention effective TFLOPS over active blocks (4*b^2*d per active block pair)",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": total_s * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg}: {c['name']} B={B} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={d} block={block}, "
+                               f"nnz={nnz} active blocks (density {nnz / mask.size:.3f})",
+                   "step": "plan_sparse_attn + sparse_attn_fwd" if static_plan is None else "sparse_attn_fwd (plan reused)",
+                   "partitions": side["balanced"]["cus_seen"] if args.partitions == 0 else args.partitions},
+        "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "kernel_ms": kern_avg,
+        "kernel_ms_min": float(np.min(kern_ms)),
+        "plan_ms": float(np.mean(plan_us)) / 1e3 if plan_us else None,
+        "plan_pct_of_kernel": (float(np.mean(plan_us)) / 1e3 / kern_avg * 100.0) if plan_us else None,
+        "imbalance": side,
+        "speedup_balanced_over_naive": side["naive"]["kernel_ms"] / side["balanced"]["kernel_ms"],
+        "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=args.cpu_budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
