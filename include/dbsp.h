@@ -41,15 +41,22 @@ typedef enum dbsp_status {
 /* Opaque, library-owned plan.  Immutable after creation except for its scratch buffers. */
 typedef struct dbsp_plan dbsp_plan;
 
-enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1 };
+enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1, DBSP_MODE_ROUNDS = 2 };
 enum { DBSP_PLAN_HOST_ONLY = 1 }; /* flags bit: build the plan on the host only (no device, no upload);
                                      such a plan cannot be passed to sparse_attn_fwd */
 
 typedef struct dbsp_plan_opts {
-  int32_t num_partitions; /* P >= 1; 0 -> number of compute units of the current device (256 when no device) */
+  int32_t num_partitions; /* P >= 1; 0 -> number of compute units of the current device (256 when no device),
+                             times 4 when block <= 64 (those workgroups are one wave each) */
   int32_t mode;           /* DBSP_MODE_BALANCED: greedy longest-first placement (Alg. 1, first loop);
                              DBSP_MODE_NAIVE: items in row-major order dealt in contiguous runs of
-                             ceil(n_items / P) -- the unbalanced baseline rho_s is quoted against */
+                             ceil(n_items / P) -- the unbalanced baseline rho_s is quoted against;
+                             DBSP_MODE_ROUNDS: the greedy applied round by round: heads in descending
+                             order of their block count (Alg. 1's sort), their items cut into consecutive
+                             rounds of P, and inside a round the k-th heaviest item goes to the k-th
+                             least-loaded partition.  All partitions then work on the same head at about
+                             the same time, so KV blocks are reused from L2: balance traded for locality,
+                             the trade-off the paper steers with its reward factor R_b */
   int32_t max_item_len;   /* split threshold in blocks: a row with more active blocks is cut into
                              ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (4 P)); < 0 -> never split */
   int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
@@ -70,7 +77,8 @@ typedef struct dbsp_plan_opts {
  * KV-block index list per row; work items (head, q_block, kv_begin, kv_end) in row-major order
  * with long rows split; greedy placement: stable sort by weight descending, each item to the
  * partition with the smallest accumulated weight (ties: lowest index); each partition's list
- * in ascending item order; rho_s of the naive and the greedy placement (Eq. 1 with one period).
+ * in ascending item order (round order for DBSP_MODE_ROUNDS); rho_s of the naive, the greedy and
+ * the chosen placement (Eq. 1 with one period).
  * Unless DBSP_PLAN_HOST_ONLY is set, the arrays are then copied to the current device and
  * scratch for split rows and busy-time capture is allocated there.
  * Errors: DBSP_EINVAL, DBSP_ENOMEM, DBSP_EHIP.  Rows with no active block are legal.
@@ -113,7 +121,7 @@ enum dbsp_plan_array {
                                chunks of split rows, in item order                                    */
   DBSP_SPLIT_ROWS = 4,      /* int32 [n_split*4] (row, first_slot, n_chunks, 0)                       */
   DBSP_PART_PTR = 5,        /* int32 [P + 1]     offsets into PART_ITEMS                              */
-  DBSP_PART_ITEMS = 6,      /* int32 [n_items]   item ids of each partition, ascending                */
+  DBSP_PART_ITEMS = 6,      /* int32 [n_items]   item ids of each partition, in processing order      */
   DBSP_PART_LOAD = 7,       /* int64 [P]         active blocks per partition (pure block counts)      */
   DBSP_BLOCKS_PER_HEAD = 8, /* int64 [H]         active blocks per head                               */
   DBSP_ROW_CNT = 9,         /* int32 [H*nQ]      active blocks per row                                */
@@ -124,10 +132,12 @@ enum dbsp_plan_array {
 int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_t* count);
 
 /* dbsp_plan_stats: any output pointer may be NULL.  rho_* are Eq. 1 (one period) on pure block
- * counts for the naive and the greedy placement of the SAME item list; plan_usec is the host
- * time spent inside plan_sparse_attn (including the device upload). */
-int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, int64_t* nnz,
-                    int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
+ * counts of the SAME item list under three placements: naive, greedy longest-first (balanced),
+ * and the one this plan uses (rho_plan; equals one of the other two unless the mode is
+ * DBSP_MODE_ROUNDS).  plan_usec is the host time spent inside plan_sparse_attn (including the
+ * device upload). */
+int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, double* rho_plan,
+                    int64_t* nnz, int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
                     double* plan_usec);
 
 /* dbsp_plan_busy: per-partition busy time of the LAST sparse_attn_fwd on this plan.

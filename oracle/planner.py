@@ -35,6 +35,7 @@ import numpy as np
 
 MODE_BALANCED = 0
 MODE_NAIVE = 1
+MODE_ROUNDS = 2
 
 
 def row_counts(mask):
@@ -131,6 +132,35 @@ def naive_partition(n_items: int, P: int):
     return [i // run for i in range(n_items)]
 
 
+def rounds_partition(item_heads, weights, blocks_per_head, P: int):
+    """Round-based greedy placement (locality-preserving variant of the greedy of Alg. 1).
+
+    Heads are taken in descending order of their dense-block count (Alg. 1's sort of
+    blocks_per_head; stable).  Their items, in generation order, form one sequence that is
+    cut into consecutive rounds of P items.  Inside a round the k-th heaviest item (stable)
+    goes to the k-th least-loaded partition (ties: lowest index), so every partition gets at
+    most one item per round and all partitions work on the same head at about the same
+    time.  This trades a little balance for data reuse, the trade-off the paper steers with
+    its reward factor R_b (Methodology, "Block-level Partitioning", overhead mitigation).
+    Returns (assignment per item, the item sequence).
+    """
+    H = len(blocks_per_head)
+    head_order = sorted(range(H), key=lambda h: -blocks_per_head[h])
+    by_head = [[] for _ in range(H)]
+    for i, h in enumerate(item_heads):
+        by_head[h].append(i)
+    seq = [i for h in head_order for i in by_head[h]]
+    assign = [0] * len(weights)
+    load = [0] * P
+    for r0 in range(0, len(seq), P):
+        idx = sorted(seq[r0:r0 + P], key=lambda i: -weights[i])
+        parts = sorted(range(P), key=lambda g: load[g])
+        for k, i in enumerate(idx):
+            assign[i] = parts[k]
+            load[parts[k]] += weights[i]
+    return assign, seq
+
+
 def imbalance_ratio(work):
     """Eq. 1: sum_i max_g b[i][g] / (sum_{i,g} b[i][g] / |G|); work is [periods][partitions]."""
     work = [[int(x) for x in row] for row in work]
@@ -173,12 +203,19 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
 
     rho_bal = imbalance_ratio([loads_of(lpt_assign)])
     rho_naive = imbalance_ratio([loads_of(nv_assign)])
-    assign = lpt_assign if mode == MODE_BALANCED else nv_assign
+    order = range(len(items))
+    if mode == MODE_BALANCED:
+        assign = lpt_assign
+    elif mode == MODE_NAIVE:
+        assign = nv_assign
+    else:
+        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P)
 
-    # per-partition lists, each in ascending item id = ascending (head, q_block, kv_begin)
+    # per-partition lists: ascending item id = ascending (head, q_block, kv_begin); for the
+    # round-based placement, the order of the rounds
     lists = [[] for _ in range(P)]
-    for i, g in enumerate(assign):
-        lists[g].append(i)
+    for i in order:
+        lists[assign[i]].append(i)
     part_ptr = [0]
     part_items = []
     for g in range(P):
@@ -192,5 +229,5 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
         items=items, item_slot=slot, split_rows=split_rows,
         part_ptr=part_ptr, part_items=part_items,
         part_load=loads_of(assign),
-        rho_naive=rho_naive, rho_balanced=rho_bal,
+        rho_naive=rho_naive, rho_balanced=rho_bal, rho_plan=imbalance_ratio([loads_of(assign)]),
     )

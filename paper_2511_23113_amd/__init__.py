@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     DbspError,
     MODE_BALANCED,
     MODE_NAIVE,
+    MODE_ROUNDS,
     Plan,
     imbalance_ratio,
     load_library,

@@ -15,7 +15,7 @@ import numpy as np
 from . import build as _build
 
 DBSP_OK, DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM, DBSP_EHIP = 0, -1, -2, -3, -4
-MODE_BALANCED, MODE_NAIVE = 0, 1
+MODE_BALANCED, MODE_NAIVE, MODE_ROUNDS = 0, 1, 2
 PLAN_HOST_ONLY = 1
 
 ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, BLOCKS_PER_HEAD, ROW_CNT, EMPTY_ROWS = range(11)
@@ -59,7 +59,7 @@ def load_library(path: str | None = None):
     lib.imbalance_ratio.restype = C.c_int
     lib.dbsp_plan_get.argtypes = [vp, i32, C.POINTER(vp), i64p]
     lib.dbsp_plan_get.restype = C.c_int
-    lib.dbsp_plan_stats.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), i64p, i64p,
+    lib.dbsp_plan_stats.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), i64p, i64p,
                                     C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
     lib.dbsp_plan_stats.restype = C.c_int
     lib.dbsp_plan_busy.argtypes = [vp, vp, vp, vp]
@@ -102,12 +102,12 @@ class Plan:
         return np.frombuffer(buf, dtype=dt).copy()
 
     def stats(self) -> dict:
-        rn, rb, pu = C.c_double(), C.c_double(), C.c_double()
+        rn, rb, rp, pu = C.c_double(), C.c_double(), C.c_double(), C.c_double()
         nnz, ni = C.c_int64(), C.c_int64()
         P, L = C.c_int32(), C.c_int32()
-        _check(load_library().dbsp_plan_stats(self.handle, C.byref(rn), C.byref(rb), C.byref(nnz), C.byref(ni),
+        _check(load_library().dbsp_plan_stats(self.handle, C.byref(rn), C.byref(rb), C.byref(rp), C.byref(nnz), C.byref(ni),
                                               C.byref(P), C.byref(L), C.byref(pu)))
-        return dict(rho_naive=rn.value, rho_balanced=rb.value, nnz=nnz.value, n_items=ni.value,
+        return dict(rho_naive=rn.value, rho_balanced=rb.value, rho_plan=rp.value, nnz=nnz.value, n_items=ni.value,
                     num_partitions=P.value, max_item_len=L.value, plan_usec=pu.value)
 
     def busy(self, stream=None):

@@ -110,7 +110,7 @@ int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   dbsp_plan_opts o;
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
-  if (o.num_partitions < 0 || o.item_overhead < 0 || (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE) ||
+  if (o.num_partitions < 0 || o.item_overhead < 0 || (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS) ||
       (o.flags & ~DBSP_PLAN_HOST_ONLY))
     return fail(DBSP_EINVAL, "plan_sparse_attn: bad option (partitions < 0, overhead < 0, unknown mode or flag)");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
@@ -125,6 +125,8 @@ int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
       else
         (void)hipGetLastError();
     }
+    // a 64-token block is served by a one-wave workgroup: four of them fill a compute unit
+    if (block <= 64) P *= 4;
   }
   dbsp_plan* plan = new (std::nothrow) dbsp_plan();
   if (!plan) return fail(DBSP_ENOMEM, "plan_sparse_attn: out of host memory");
@@ -230,13 +232,14 @@ int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_
 #undef DBSP_ARR
 }
 
-int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, int64_t* nnz,
-                    int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
+int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, double* rho_plan,
+                    int64_t* nnz, int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
                     double* plan_usec) {
   if (!plan) return fail(DBSP_EINVAL, "dbsp_plan_stats: null plan");
   const dbsp_host_plan& hp = plan->host;
   if (rho_naive) *rho_naive = hp.rho_naive;
   if (rho_balanced) *rho_balanced = hp.rho_balanced;
+  if (rho_plan) *rho_plan = hp.rho_mode;
   if (nnz) *nnz = hp.nnz;
   if (n_items) *n_items = hp.n_items();
   if (num_partitions) *num_partitions = hp.P;

@@ -8,7 +8,7 @@
 // "Block-wise Sparse Attention"), where only the dense blocks of the mask are visited, so an
 // item costs its number of dense blocks.
 //
-// Work split inside a workgroup (wave = 64 lanes, lane = 32*g + r, 16-lane group index hh):
+// Work split inside a workgroup (wave = 64 lanes, lane = 32*g + r):
 //   * waves form a (query half) x (key half) grid: wave (a, c) owns 64 query columns and, of
 //     every KV block, the keys [c*KW, (c+1)*KW).  Each wave keeps its own running softmax
 //     statistics over its key half; the two key halves are combined once per item.
@@ -20,9 +20,14 @@
 //     for that 16-key step.  The matching V^T operand comes from two transposing LDS reads
 //     (ds_read_b64_tr_b16) of row-major V: in a group of 16 lanes, lane 4j+a supplies the
 //     address of 4 consecutive d-values of key j, and lane i receives d-value i of 4 keys.
+// Software pipeline (one wave per SIMD, so overlap has to come from one instruction stream):
+//   the unit of work is 32 keys x 64 queries.  Step i issues, as independent work,
+//     the MFMAs of  K Q^T of unit i   and of  V^T P^T of unit i-2,  and
+//     the VALU work of the softmax of unit i-1,
+//   so matrix and vector pipes run side by side; S and P are double buffered in registers.
 // Data movement:
-//   * K and V blocks go HBM/L2 -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane,
-//     no VGPR staging), double buffered: the loads of block j+1 fly while block j is computed.
+//   * K and V blocks go L2 -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
+//     VGPR staging), double buffered and issued a few at a time between MFMAs.
 //   * LDS tiles are unpadded; 16-byte chunks are XOR-swizzled inside each row instead (the
 //     permutation is applied to the per-lane global source address, the LDS side of the copy
 //     is linear): K by the row index so that the 16-byte operand reads of 16 lanes (16
@@ -38,7 +43,6 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -47,8 +51,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// the running max is raised only when a query's max grows by more than this many powers of two
+constexpr float RESCALE_LOG2 = 6.0f;
+
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
-#define GLOBAL_PTR(T) __attribute__((address_space(1))) T*
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   f32x2 f = {a, b};
@@ -58,33 +64,72 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
-__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+// Exchange between the lane pair (r, r + 32) with one VALU swap of the two 32-lane halves (no
+// LDS traffic): v_permlane32_swap swaps the upper half of its first operand with the lower half
+// of its second; fed two copies of x it leaves {lo, lo} in the first and {hi, hi} in the second.
+// Inline assembly: the compiler's builtin returns the first register for both results.  The
+// s_nop's cover the wait states between a VALU write and the swap's read of the same register,
+// and between the swap and its consumers, which the compiler cannot insert inside an asm block.
+struct halves { float lo, hi; };
+__device__ __forceinline__ halves swap_halves(float x) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return {a, b};
+}
+__device__ __forceinline__ float max_xor32(float x) {
+  const halves sw = swap_halves(x);
+  return fmaxf(sw.lo, sw.hi);
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+  const halves sw = swap_halves(x);
+  return sw.lo + sw.hi;
+}
+
+// One wave copies 64 x 16 bytes from global memory straight into LDS: lane i reads 16 bytes at
+// base + voff(i) and they land at LDS byte address lds_dst + 16*i (M0 carries lds_dst).  Inline
+// assembly keeps the copy outside the compiler's wait-count bookkeeping: the kernel waits for
+// it explicitly (s_waitcnt vmcnt(0)) right before the barrier that publishes the tile.  No
+// "memory" clobber: LDS reads of the OTHER buffer may be scheduled across the copy.
+__device__ __forceinline__ void copy16_to_lds(const unsigned char* base, uint32_t voff, uint32_t lds_dst) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_dst), "v"(voff), "s"(base));
+}
 
 template <int BLK, int D>
 struct Cfg {
   static constexpr int NQH = BLK / 64;      // 64-query groups
-  static constexpr int NKH = 2;             // key halves
+  static constexpr int NKH = BLK / 64;      // 64-key groups of a KV block, one per wave column
   static constexpr int NW = NQH * NKH;      // waves
   static constexpr int NT = NW * 64;        // threads
   static constexpr int KW = BLK / NKH;      // keys per wave per KV block
-  static constexpr int KTW = KW / 32;       // 32-key tiles per wave
+  static constexpr int U = KW / 32;         // 32-key pipeline units per wave per KV block (always 2)
+  static_assert(U == 2, "the pipeline below assumes two units per KV block");
   static constexpr int QT = 2;              // 32-query tiles per wave
   static constexpr int DT = D / 32;         // 32-wide tiles of the head dim
   static constexpr int KS_QK = D / 16;      // k-steps of K Q^T
-  static constexpr int KS_PV = KW / 16;     // k-steps of V^T P^T (per wave)
   static constexpr int NCH = D / 8;         // 16-byte chunks per row
   static constexpr int RPL = 128 / D;       // rows per 256 bytes (one sweep over the 64 LDS banks)
   static constexpr int ROW_BYTES = D * 2;
   static constexpr int TILE_BYTES = BLK * D * 2;
   static constexpr int LOADS = (BLK * D / 8 / 64) / NW;   // 1-KiB direct-to-LDS copies per wave per tile
-  static constexpr int LDS_BYTES = 4 * TILE_BYTES;        // K[2], V[2]
-  static constexpr int XCH_BYTES = NW * (QT * (DT / 2) * 16 * 64 * 4 + QT * 2 * 64 * 4);  // end-of-item exchange
+  static constexpr int STEP_ROWS = NW * 64 / NCH;         // rows between consecutive copies of one wave
+  // K's swizzle has period NCH*RPL rows; if STEP_ROWS is not a multiple of it, copies alternate
+  // between SRC_VARIANTS per-lane source offsets
+  static constexpr int SRC_VARIANTS = (STEP_ROWS % (NCH * RPL) == 0) ? 1 : (NCH * RPL) / STEP_ROWS;
+  static_assert(STEP_ROWS % (4 * RPL) == 0, "V's swizzle period must divide the copy step");
+  static constexpr int NKB = 2, NVB = 2;
+  static constexpr int LDS_BYTES = (NKB + NVB) * TILE_BYTES;
+  static constexpr int XCH_BYTES = (NKH == 1) ? 0 : NW * (QT * (DT / 2) * 16 * 64 * 4 + QT * 2 * 64 * 4);  // end-of-item exchange
   static_assert(XCH_BYTES <= LDS_BYTES, "exchange area must fit in the tile buffers");
   static_assert(DT % 2 == 0, "the head dim is split between the two key-half waves at the end of an item");
 };
 
 template <int BLK, int D>
-__global__ __launch_bounds__(BLK * 2) void dbsp_fwd_kernel(
+__global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
     const dbsp_fwd_params p, const int32_t* __restrict__ g_row_ptr, const int32_t* __restrict__ g_kv_idx,
     const int4* __restrict__ g_items, const int32_t* __restrict__ g_item_slot,
     const int32_t* __restrict__ g_part_ptr, const int32_t* __restrict__ g_part_items) {
@@ -92,8 +137,8 @@ __global__ __launch_bounds__(BLK * 2) void dbsp_fwd_kernel(
   // arguments let the compiler fetch them through the scalar unit
   using C = Cfg<BLK, D>;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-  // byte offsets inside the dynamic LDS block
-  constexpr int K_OFF = 0, V_OFF = 2 * C::TILE_BYTES;
+  constexpr int K_OFF = 0, V_OFF = C::NKB * C::TILE_BYTES;   // byte offsets inside the dynamic LDS block
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
 
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -103,24 +148,31 @@ __global__ __launch_bounds__(BLK * 2) void dbsp_fwd_kernel(
   const float c = p.scale_log2;
 
   // ---- per-lane constants -------------------------------------------------------------
-  // direct-to-LDS copies: copy i of this wave fills LDS chunks [(i*NW + w)*64, +64) of a tile
-  uint32_t k_src[C::LOADS], v_src[C::LOADS];
+  // direct-to-LDS copies: copy i of this wave fills LDS chunks [(i*NW + w)*64, +64) of a tile.
+  // The LDS tile is a linear image of the global tile except for the chunk swizzle inside a
+  // row, and consecutive copies of a wave are STEP_ROWS rows apart; with STEP_ROWS a multiple
+  // of the swizzle period the per-lane source offset is the same for every copy.
+  uint32_t k_src[C::SRC_VARIANTS], v_src;
+  {
 #pragma unroll
-  for (int i = 0; i < C::LOADS; ++i) {
-    const int pc = (i * C::NW + w) * 64 + l;            // physical chunk
+    for (int i = 0; i < C::SRC_VARIANTS; ++i) {
+      const int pc = (i * C::NW + w) * 64 + l;          // physical chunk of copy i
+      const int row = pc / C::NCH, pch = pc % C::NCH;
+      const int kch = pch ^ ((row / C::RPL) % C::NCH);
+      k_src[i] = (row - i * C::STEP_ROWS) * C::ROW_BYTES + kch * 16;
+    }
+    const int pc = w * 64 + l;
     const int row = pc / C::NCH, pch = pc % C::NCH;
-    const int kch = pch ^ ((row / C::RPL) % C::NCH);
-    const int vch = pch ^ (((row / C::RPL) % (C::NCH / 4)) << 2);
-    k_src[i] = row * C::ROW_BYTES + kch * 16;
-    v_src[i] = row * C::ROW_BYTES + vch * 16;
+    v_src = row * C::ROW_BYTES + ((pch ^ (((row / C::RPL) % (C::NCH / 4)) << 2)) * 16);
   }
-  // K operand reads: key row KW*wc + 32*kt + r, logical chunk 2*ks + g
-  uint32_t k_rd[C::KS_QK];
+  // K operand reads: key row KW*wc + 32*unit + r, logical chunk 2*ks + g, physical chunk
+  // (2*ks + g) ^ sw.  Bits 1..3 of the chunk index are ks ^ (sw >> 1), so the address of
+  // k-step ks is k_rd0 ^ (ks << 5).
+  uint32_t k_rd0;
   {
     const int row = C::KW * wc + r;
     const int sw = (row / C::RPL) % C::NCH;
-#pragma unroll
-    for (int ks = 0; ks < C::KS_QK; ++ks) k_rd[ks] = row * C::ROW_BYTES + (((2 * ks + g) ^ sw) << 4);
+    k_rd0 = row * C::ROW_BYTES + ((g ^ sw) << 4);
   }
   // V^T operand reads (transposing): lane 4j+a of a 16-lane group addresses key j, d-quad a
   uint32_t v_rd[C::DT];
@@ -142,23 +194,30 @@ __global__ __launch_bounds__(BLK * 2) void dbsp_fwd_kernel(
       const int4 item = g_items[it];
       const int h = item.x, I = item.y;
       const int slot = g_item_slot[it];
-      const int32_t* __restrict__ kv = g_kv_idx + g_row_ptr[h * p.nQ + I];
+      const int32_t* __restrict__ kv = g_kv_idx + g_row_ptr[h * p.nQ + I] + item.z;   // this item's KV blocks
+      const int n_tiles = item.w - item.z;
+      const int NU = n_tiles * C::U;                                                  // pipeline units
       const int64_t bh = (int64_t)bb * p.H + h;
       const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k + bh * p.nK * BLK * D);
       const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v + bh * p.nK * BLK * D);
 
-      auto issue_loads = [&](int J, int buf) {
-        const unsigned char* kt = kbase + (int64_t)J * C::TILE_BYTES;
-        const unsigned char* vt = vbase + (int64_t)J * C::TILE_BYTES;
+      // copies [i0, i1) of one tile of this wave
+      auto copy_k = [&](int J, int buf, int i0, int i1) {
+        const unsigned char* src = kbase + (int64_t)J * C::TILE_BYTES;
 #pragma unroll
-        for (int i = 0; i < C::LOADS; ++i) {
-          const int dst = buf * C::TILE_BYTES + (i * C::NW + w) * 1024;
-          __builtin_amdgcn_global_load_lds((const GLOBAL_PTR(void))(kt + k_src[i]), (LDS_PTR(void))(lds + K_OFF + dst), 16, 0, 0);
-          __builtin_amdgcn_global_load_lds((const GLOBAL_PTR(void))(vt + v_src[i]), (LDS_PTR(void))(lds + V_OFF + dst), 16, 0, 0);
-        }
+        for (int i = i0; i < i1; ++i)
+          copy16_to_lds(src + i * C::STEP_ROWS * C::ROW_BYTES, k_src[i % C::SRC_VARIANTS],
+                        lds_base + K_OFF + buf * C::TILE_BYTES + (i * C::NW + w) * 1024);
+      };
+      auto copy_v = [&](int J, int buf, int i0, int i1) {
+        const unsigned char* src = vbase + (int64_t)J * C::TILE_BYTES;
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+          copy16_to_lds(src + i * C::STEP_ROWS * C::ROW_BYTES, v_src,
+                        lds_base + V_OFF + buf * C::TILE_BYTES + (i * C::NW + w) * 1024);
       };
 
-      issue_loads(kv[item.z], 0);
+      copy_k(kv[0], 0, 0, C::LOADS);   // K of the first block; V of block T is copied during block T's steps
 
       // Q^T operands of this wave's 64 queries: lane (r, g) holds q[32*qt + r][16ks + 8g .. +7]
       const int q0 = 64 * wa;
@@ -170,6 +229,14 @@ __global__ __launch_bounds__(BLK * 2) void dbsp_fwd_kernel(
         for (int ks = 0; ks < C::KS_QK; ++ks)
           qreg[qt][ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 16 * ks + 8 * g));
       }
+      // Park Q in accumulation registers (the MFMA reads its B operand from there directly): the
+      // arch-VGPR file is the scarce one in the KV loop.  This also makes the compiler wait for
+      // the Q loads here, before the loop, rather than at their first use inside it (a wait
+      // inside the loop would also wait for the in-flight tile copies: same counter).
+#pragma unroll
+      for (int qt = 0; qt < C::QT; ++qt)
+#pragma unroll
+        for (int ks = 0; ks < C::KS_QK; ++ks) asm volatile("" : "+a"(qreg[qt][ks]));
 
       f32x16 oacc[C::DT][C::QT];
 #pragma unroll
@@ -182,161 +249,261 @@ __global__ __launch_bounds__(BLK * 2) void dbsp_fwd_kernel(
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
 
-      for (int j = item.z; j < item.w; ++j) {
-        const int buf = (j - item.z) & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies of block j have landed
-        __syncthreads();                      // ... and everybody's; all waves are done with block j-1
-        if (j + 1 < item.w) issue_loads(kv[j + 1], buf ^ 1);
+      // double-buffered pipeline registers: S[x] = scores of the unit whose K Q^T ran in a step of
+      // parity x; Pb[x] = its probabilities, packed to bf16 as the B operands of two 16-key steps
+      f32x16 S[2][C::QT];
+      bf16x8 Pb[2][2][C::QT];
 
-        const unsigned char* sK = lds + K_OFF + buf * C::TILE_BYTES;
-        const unsigned char* sV = lds + V_OFF + buf * C::TILE_BYTES;
+      // One pipeline step.  PAR = parity of the step; QK / SM / PV say which stages are live
+      // (all three in the steady state; fewer while the pipeline fills and drains).
+      auto step = [&](int i, auto par_tag, auto qk_tag, auto sm_tag, auto pv_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        constexpr bool QK = decltype(qk_tag)::value, SM = decltype(sm_tag)::value, PV = decltype(pv_tag)::value;
+        // with two units per KV block the step parity is also the unit's half of the block
+        constexpr int HALF = (C::U == 1) ? 0 : PAR;
+        const int Tq = i / C::U, hq = HALF;                  // unit of the K Q^T stage
+        const int Tp = (i - 2) / C::U, hp = HALF;            // unit of the V^T P^T stage
+        if (C::U == 1 || PAR == 0) {
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's copies issued so far have landed
+          __syncthreads();   // ... and everybody's; every wave is past the steps that read the buffers refilled next
+        }
+        // tile copies of this step: K of block Tq+1 (clamped at the end: one redundant copy per
+        // item) and V of block Tq, split over the U steps of block Tq
+        const int Jk = kv[(Tq + 1 < n_tiles) ? Tq + 1 : n_tiles - 1];
+        const int Jv = kv[(Tq < n_tiles) ? Tq : n_tiles - 1];
+        const int kbuf_next = (Tq + 1) % C::NKB, vbuf_this = Tq % C::NVB;
+        constexpr int CP = C::LOADS / C::U;                  // copies of each tensor per step
+        const int cp0 = hq * CP;
 
-        // S^T = K Q^T : [KW keys of this wave] x [64 queries of this wave]
-        f32x16 sacc[C::KTW][C::QT];
+        // LDS operand reads of this step
+        bf16x8 ka[C::KS_QK];
+        const unsigned char* sK = lds + K_OFF + (Tq % C::NKB) * C::TILE_BYTES + hq * 32 * C::ROW_BYTES;
+        constexpr int PF_K = C::KS_QK / 2;   // K operand reads run this many k-steps ahead of their MFMAs
+        auto read_k = [&](int ks) { ka[ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(sK + (k_rd0 ^ (ks << 5)))); };
+        if constexpr (QK) {
 #pragma unroll
-        for (int kt = 0; kt < C::KTW; ++kt)
+          for (int ks = 0; ks < PF_K; ++ks) read_k(ks);
+        }
+        s16x4 va[2][C::DT][2];
+        const unsigned char* sV = lds + V_OFF + (Tp % C::NVB) * C::TILE_BYTES + hp * 32 * C::ROW_BYTES;
+        auto read_v = [&](int ks) {
+#pragma unroll
+          for (int dt = 0; dt < C::DT; ++dt) {
+            const unsigned char* vp = sV + v_rd[dt] + ks * 16 * C::ROW_BYTES;
+            va[ks][dt][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(vp));
+            va[ks][dt][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(vp + 8 * C::ROW_BYTES));
+          }
+        };
+        if constexpr (PV) read_v(0);
+
+        // ---- softmax of unit i-1 (VALU), reading S[1-PAR], writing Pb[1-PAR] --------------
+        bool pend = false;
+        float alpha[C::QT];
+        if constexpr (SM) {
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt) {
+            const f32x16& sv = S[1 - PAR][qt];
+            float mx0 = fmaxf(sv[0], sv[1]), mx1 = fmaxf(sv[2], sv[3]);
+#pragma unroll
+            for (int e = 4; e < 16; e += 4) {
+              mx0 = fmaxf(mx0, fmaxf(sv[e], sv[e + 1]));
+              mx1 = fmaxf(mx1, fmaxf(sv[e + 2], sv[e + 3]));
+            }
+            const float mx = max_xor32(fmaxf(mx0, mx1));
+            // The running max is raised only when some query's max grew by more than
+            // 2^RESCALE_LOG2 (in exp2 units); until then P may exceed 1 by at most that factor,
+            // which f32 / bf16 hold without loss, and the accumulator rescale is skipped.
+            const bool need = __builtin_amdgcn_ballot_w64((mx - m_run[qt]) * c > RESCALE_LOG2) != 0;
+            const float m_new = need ? fmaxf(m_run[qt], mx) : m_run[qt];
+            alpha[qt] = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * c);
+            pend = pend || need;
+            m_run[qt] = m_new;
+            const float mc = m_new * c;
+            float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+              float pe[8];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + e], c, -mc));
+              ls0 += (pe[0] + pe[1]) + (pe[2] + pe[3]);
+              ls1 += (pe[4] + pe[5]) + (pe[6] + pe[7]);
+              u32x4 pb;
+              pb.x = pack_bf16x2(pe[0], pe[1]);
+              pb.y = pack_bf16x2(pe[2], pe[3]);
+              pb.z = pack_bf16x2(pe[4], pe[5]);
+              pb.w = pack_bf16x2(pe[6], pe[7]);
+              Pb[1 - PAR][hf][qt] = as_bf16x8(pb);
+            }
+            l_run[qt] = l_run[qt] * alpha[qt] + (ls0 + ls1);
+          }
+        }
+
+        // ---- MFMA work: V^T P^T of unit i-2 (operands read above) and K Q^T of unit i ------
+        if constexpr (PV) {
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            if (ks == 0) read_v(1);
+#pragma unroll
+            for (int dt = 0; dt < C::DT; ++dt) {
+              const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[ks][dt][0], va[ks][dt][1], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+              for (int qt = 0; qt < C::QT; ++qt)
+                oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[PAR][ks][qt], oacc[dt][qt], 0, 0, 0);
+              if constexpr (QK) {   // a tile copy after every few MFMAs
+                const int n = ks * C::DT + dt;
+                if (n < CP) copy_k(Jk, kbuf_next, cp0 + n, cp0 + n + 1);
+              }
+            }
+          }
+        }
+        if constexpr (QK) {
+          if constexpr (!PV) copy_k(Jk, kbuf_next, cp0, cp0 + CP);
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kt][qt][i] = 0.f;
+            for (int e = 0; e < 16; ++e) S[PAR][qt][e] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < C::KS_QK; ++ks) {
-#pragma unroll
-          for (int kt = 0; kt < C::KTW; ++kt) {
-            const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(sK + k_rd[ks] + kt * 32 * C::ROW_BYTES));
+          for (int ks = 0; ks < C::KS_QK; ++ks) {
+            if (ks + PF_K < C::KS_QK) read_k(ks + PF_K);
 #pragma unroll
             for (int qt = 0; qt < C::QT; ++qt)
-              sacc[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[kt][qt], 0, 0, 0);
+              S[PAR][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qt][ks], S[PAR][qt], 0, 0, 0);
+            if (ks < CP) copy_v(Jv, vbuf_this, cp0 + ks, cp0 + ks + 1);
           }
+          if constexpr (C::KS_QK < CP) copy_v(Jv, vbuf_this, cp0 + C::KS_QK, cp0 + CP);
+          // The scores are consumed by VALU code in the next step: move them to arch VGPRs now.
+          // (Accumulation registers are fully booked by O^T, Q^T and the scores being accumulated.)
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt) asm volatile("" : "+v"(S[PAR][qt]));
         }
 
-        // online softmax over this wave's keys (per query = per lane pair r, r+32)
-#pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt) {
-          float mx = sacc[0][qt][0];
-#pragma unroll
-          for (int kt = 0; kt < C::KTW; ++kt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kt][qt][i]);
-          mx = fmaxf(mx, xor32(mx));
-          const float m_new = fmaxf(m_run[qt], mx);
-          const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * c);
-          const float mc = m_new * c;
-          m_run[qt] = m_new;
-          float lsum = 0.f;
-#pragma unroll
-          for (int kt = 0; kt < C::KTW; ++kt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt][qt][i], c, -mc));
-              sacc[kt][qt][i] = pe;
-              lsum += pe;
-            }
-          l_run[qt] = l_run[qt] * alpha + lsum;
-#pragma unroll
-          for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[dt][qt][i] *= alpha;
-        }
-
-        // O^T += V^T P^T
-#pragma unroll
-        for (int ks = 0; ks < C::KS_PV; ++ks) {
-          const int kt = ks >> 1, hf = ks & 1;
-          bf16x8 bp[C::QT];
+        // ---- deferred accumulator rescale: after V^T P^T of unit i-2, before that of unit i-1 --
+        if constexpr (SM) {
+          // pin the softmax results here: otherwise the compiler sinks the exponentials below the
+          // (rarely taken) branch, out of the block whose MFMAs they are meant to overlap with
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt) {
-            u32x4 pb;
-            pb.x = pack_bf16x2(sacc[kt][qt][8 * hf + 0], sacc[kt][qt][8 * hf + 1]);
-            pb.y = pack_bf16x2(sacc[kt][qt][8 * hf + 2], sacc[kt][qt][8 * hf + 3]);
-            pb.z = pack_bf16x2(sacc[kt][qt][8 * hf + 4], sacc[kt][qt][8 * hf + 5]);
-            pb.w = pack_bf16x2(sacc[kt][qt][8 * hf + 6], sacc[kt][qt][8 * hf + 7]);
-            bp[qt] = as_bf16x8(pb);
+            asm volatile("" ::"v"(Pb[1 - PAR][0][qt]), "v"(Pb[1 - PAR][1][qt]), "v"(l_run[qt]));
           }
-#pragma unroll
-          for (int dt = 0; dt < C::DT; ++dt) {
-            const unsigned char* va = sV + v_rd[dt] + ks * 16 * C::ROW_BYTES;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(va));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(va + 8 * C::ROW_BYTES));
-            const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          if (pend) {
 #pragma unroll
             for (int qt = 0; qt < C::QT; ++qt)
-              oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bp[qt], oacc[dt][qt], 0, 0, 0);
-          }
-        }
-      }
-
-      // ---- combine the two key halves: wave (a, c) finalises d-tiles [c*DT/2, (c+1)*DT/2) ----
-      __syncthreads();   // every wave is done reading the K/V tiles: the buffers become the exchange area
-      constexpr int HT = C::DT / 2;
-      float* xo = reinterpret_cast<float*>(lds) + w * (C::QT * HT * 16 * 64);
-      float* xs = reinterpret_cast<float*>(lds) + C::NW * (C::QT * HT * 16 * 64) + w * (C::QT * 2 * 64);
-      const int pw = wa * C::NKH + (1 - wc);   // partner wave: same queries, other key half
-      const float* yo = reinterpret_cast<const float*>(lds) + pw * (C::QT * HT * 16 * 64);
-      const float* ys = reinterpret_cast<const float*>(lds) + C::NW * (C::QT * HT * 16 * 64) + pw * (C::QT * 2 * 64);
-      const int64_t tok0 = bh * p.nQ * BLK + (int64_t)I * BLK + q0 + r;
-      const int64_t ps = (int64_t)bb * p.n_slots + slot;
-
-      // WC is this wave's key half as a compile-time constant, so that the accumulator tiles
-      // are addressed with constant indices (they must stay in registers)
-      auto finish = [&](auto wc_tag) {
-        constexpr int WC = decltype(wc_tag)::value;
-        float l_full[C::QT];
 #pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt) {
-          l_full[qt] = l_run[qt] + xor32(l_run[qt]);
-          xs[(2 * qt + 0) * 64 + l] = m_run[qt];
-          xs[(2 * qt + 1) * 64 + l] = l_full[qt];
+              for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-          for (int hx = 0; hx < HT; ++hx)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) xo[((qt * HT + hx) * 16 + i) * 64 + l] = oacc[(1 - WC) * HT + hx][qt][i];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt) {
-          const float mp = ys[(2 * qt + 0) * 64 + l], lp = ys[(2 * qt + 1) * 64 + l];
-          const float mt = fmaxf(m_run[qt], mp);
-          const float fs = __builtin_amdgcn_exp2f((m_run[qt] - mt) * c);
-          const float fp = __builtin_amdgcn_exp2f((mp - mt) * c);
-          const float lt = l_full[qt] * fs + lp * fp;
-          const float inv = 1.0f / lt;
-          const float fsi = fs * inv, fpi = fp * inv;
-          const int64_t tok = tok0 + 32 * qt;
-#pragma unroll
-          for (int hx = 0; hx < HT; ++hx) {
-            float res[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              res[i] = oacc[WC * HT + hx][qt][i] * fsi + yo[((qt * HT + hx) * 16 + i) * 64 + l] * fpi;
-            if (slot < 0) {
-              uint16_t* orow = p.o + tok * D + 32 * (WC * HT + hx) + 4 * g;
-#pragma unroll
-              for (int i4 = 0; i4 < 4; ++i4) {
-                u32x2 pk;
-                pk.x = pack_bf16x2(res[4 * i4 + 0], res[4 * i4 + 1]);
-                pk.y = pack_bf16x2(res[4 * i4 + 2], res[4 * i4 + 3]);
-                *reinterpret_cast<u32x2*>(orow + 8 * i4) = pk;
-              }
-            } else {
-              float* orow = p.part_o + (ps * BLK + q0 + 32 * qt + r) * D + 32 * (WC * HT + hx) + 4 * g;
-#pragma unroll
-              for (int i4 = 0; i4 < 4; ++i4) {
-                f32x4 f = {res[4 * i4 + 0], res[4 * i4 + 1], res[4 * i4 + 2], res[4 * i4 + 3]};
-                *reinterpret_cast<f32x4*>(orow + 8 * i4) = f;
-              }
-            }
-          }
-          if (WC == 0 && g == 0) {
-            const float lse = mt * p.scale + __logf(lt);
-            if (slot < 0) { if (p.lse != nullptr) p.lse[tok] = lse; }
-            else p.part_lse[ps * BLK + q0 + 32 * qt + r] = lse;
+                for (int e = 0; e < 16; ++e) oacc[dt][qt][e] *= alpha[qt];
           }
         }
       };
-      if (wc == 0) finish(std::integral_constant<int, 0>{});
-      else finish(std::integral_constant<int, 1>{});
-      __syncthreads();   // exchange area fully read before the next item's copies overwrite it
+
+      using T0 = std::integral_constant<int, 0>;
+      using T1 = std::integral_constant<int, 1>;
+      using Yes = std::true_type;
+      using No = std::false_type;
+      // fill (two steps), steady state, drain (two steps); NU is even, so parities are static
+      step(0, T0{}, Yes{}, No{}, No{});
+      step(1, T1{}, Yes{}, Yes{}, No{});
+      for (int i = 2; i < NU; i += 2) {
+        step(i, T0{}, Yes{}, Yes{}, Yes{});
+        step(i + 1, T1{}, Yes{}, Yes{}, Yes{});
+      }
+      step(NU, T0{}, No{}, Yes{}, Yes{});
+      step(NU + 1, T1{}, No{}, No{}, Yes{});
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant last K copy must not outlive the item
+
+      // ---- end of item: combine the key halves (if the block has two) and store ----------------
+      __syncthreads();   // every wave is done reading the K/V tiles: the buffers become the exchange area
+      const int64_t tok0 = bh * p.nQ * BLK + (int64_t)I * BLK + q0 + r;
+      const int64_t ps = (int64_t)bb * p.n_slots + slot;
+      // stores 16 values of one 32x32 tile of O^T: query tok, d = 32*dt + 8*(e/4) + 4*g + e%4
+      auto store_tile = [&](const float (&res)[16], int64_t tok, int qloc, int dt) {
+        if (slot < 0) {
+          uint16_t* orow = p.o + tok * D + 32 * dt + 4 * g;
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            u32x2 pk;
+            pk.x = pack_bf16x2(res[4 * i4 + 0], res[4 * i4 + 1]);
+            pk.y = pack_bf16x2(res[4 * i4 + 2], res[4 * i4 + 3]);
+            *reinterpret_cast<u32x2*>(orow + 8 * i4) = pk;
+          }
+        } else {
+          float* orow = p.part_o + (ps * BLK + qloc) * D + 32 * dt + 4 * g;
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            f32x4 f = {res[4 * i4 + 0], res[4 * i4 + 1], res[4 * i4 + 2], res[4 * i4 + 3]};
+            *reinterpret_cast<f32x4*>(orow + 8 * i4) = f;
+          }
+        }
+      };
+      auto store_lse = [&](float lse, int64_t tok, int qloc) {
+        if (slot < 0) { if (p.lse != nullptr) p.lse[tok] = lse; }
+        else p.part_lse[ps * BLK + qloc] = lse;
+      };
+
+      if constexpr (C::NKH == 1) {
+#pragma unroll
+        for (int qt = 0; qt < C::QT; ++qt) {
+          const float lt = sum_xor32(l_run[qt]);
+          const float inv = 1.0f / lt;
+          const int64_t tok = tok0 + 32 * qt;
+#pragma unroll
+          for (int dt = 0; dt < C::DT; ++dt) {
+            float res[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) res[e] = oacc[dt][qt][e] * inv;
+            store_tile(res, tok, q0 + 32 * qt + r, dt);
+          }
+          if (g == 0) store_lse(m_run[qt] * p.scale + __logf(lt), tok, q0 + 32 * qt + r);
+        }
+      } else {
+        // wave (a, c) finalises d-tiles [c*DT/2, (c+1)*DT/2) and hands the other half to its partner
+        constexpr int HT = C::DT / 2;
+        float* xo = reinterpret_cast<float*>(lds) + w * (C::QT * HT * 16 * 64);
+        float* xs = reinterpret_cast<float*>(lds) + C::NW * (C::QT * HT * 16 * 64) + w * (C::QT * 2 * 64);
+        const int pw = wa * C::NKH + (1 - wc);   // partner wave: same queries, other key half
+        const float* yo = reinterpret_cast<const float*>(lds) + pw * (C::QT * HT * 16 * 64);
+        const float* ys = reinterpret_cast<const float*>(lds) + C::NW * (C::QT * HT * 16 * 64) + pw * (C::QT * 2 * 64);
+        // WC is this wave's key half as a compile-time constant, so that the accumulator tiles
+        // are addressed with constant indices (they must stay in registers)
+        auto finish = [&](auto wc_tag) {
+          constexpr int WC = decltype(wc_tag)::value;
+          float l_full[C::QT];
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt) {
+            l_full[qt] = sum_xor32(l_run[qt]);
+            xs[(2 * qt + 0) * 64 + l] = m_run[qt];
+            xs[(2 * qt + 1) * 64 + l] = l_full[qt];
+#pragma unroll
+            for (int hx = 0; hx < HT; ++hx)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) xo[((qt * HT + hx) * 16 + e) * 64 + l] = oacc[(1 - WC) * HT + hx][qt][e];
+          }
+          __syncthreads();
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt) {
+            const float mp = ys[(2 * qt + 0) * 64 + l], lp = ys[(2 * qt + 1) * 64 + l];
+            const float mt = fmaxf(m_run[qt], mp);
+            const float fs = __builtin_amdgcn_exp2f((m_run[qt] - mt) * c);
+            const float fp = __builtin_amdgcn_exp2f((mp - mt) * c);
+            const float lt = l_full[qt] * fs + lp * fp;
+            const float inv = 1.0f / lt;
+            const float fsi = fs * inv, fpi = fp * inv;
+            const int64_t tok = tok0 + 32 * qt;
+#pragma unroll
+            for (int hx = 0; hx < HT; ++hx) {
+              float res[16];
+#pragma unroll
+              for (int e = 0; e < 16; ++e)
+                res[e] = oacc[WC * HT + hx][qt][e] * fsi + yo[((qt * HT + hx) * 16 + e) * 64 + l] * fpi;
+              store_tile(res, tok, q0 + 32 * qt + r, WC * HT + hx);
+            }
+            if (WC == 0 && g == 0) store_lse(mt * p.scale + __logf(lt), tok, q0 + 32 * qt + r);
+          }
+        };
+        if (wc == 0) finish(std::integral_constant<int, 0>{});
+        else finish(std::integral_constant<int, 1>{});
+        __syncthreads();   // exchange area fully read before the next item's copies overwrite it
+      }
       busy += wall_clock64() - t0;
     }
   }

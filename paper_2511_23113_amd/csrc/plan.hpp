@@ -23,7 +23,7 @@ struct dbsp_host_plan {
   std::vector<int32_t> part_items;       // [n_items]
   std::vector<int64_t> part_load;        // [P]
   int32_t n_slots = 0;
-  double rho_naive = 1.0, rho_balanced = 1.0;
+  double rho_naive = 1.0, rho_balanced = 1.0, rho_mode = 1.0;  // rho_mode: of the placement actually used
   int64_t n_items() const { return (int64_t)item_slot.size(); }
 };
 

@@ -148,6 +148,39 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       }
     }
 
+    // round-based greedy (DBSP_MODE_ROUNDS): heads in descending order of their block count
+    // (the sort of Alg. 1), their items cut into consecutive rounds of P; inside a round the
+    // k-th heaviest item goes to the k-th least-loaded partition.  Every partition works on the
+    // same head at about the same time, which is what lets the KV blocks be reused from L2.
+    std::vector<int32_t> assign_rounds, seq;
+    if (mode == DBSP_MODE_ROUNDS) {
+      auto weight = [&](int64_t i) { return (int64_t)(hp.items[4 * i + 3] - hp.items[4 * i + 2]) + item_overhead; };
+      std::vector<int32_t> head_order(H);
+      for (int32_t h = 0; h < H; ++h) head_order[h] = h;
+      std::stable_sort(head_order.begin(), head_order.end(),
+                       [&](int32_t a, int32_t b) { return hp.blocks_per_head[a] > hp.blocks_per_head[b]; });
+      std::vector<int64_t> head_begin(H + 1, 0);   // items are generated head-major
+      for (int64_t i = 0; i < n_items; ++i) head_begin[hp.items[4 * i] + 1]++;
+      for (int32_t h = 0; h < H; ++h) head_begin[h + 1] += head_begin[h];
+      seq.reserve(n_items);
+      for (int32_t h : head_order)
+        for (int64_t i = head_begin[h]; i < head_begin[h + 1]; ++i) seq.push_back((int32_t)i);
+      assign_rounds.assign(n_items, 0);
+      std::vector<int64_t> load(P, 0);
+      std::vector<int32_t> parts(P), idx;
+      for (int64_t r0 = 0; r0 < n_items; r0 += P) {
+        const int64_t r1 = std::min<int64_t>(n_items, r0 + P);
+        idx.assign(seq.begin() + r0, seq.begin() + r1);
+        std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) { return weight(a) > weight(b); });
+        for (int32_t g = 0; g < P; ++g) parts[g] = g;
+        std::stable_sort(parts.begin(), parts.end(), [&](int32_t a, int32_t b) { return load[a] < load[b]; });
+        for (size_t k = 0; k < idx.size(); ++k) {
+          assign_rounds[idx[k]] = parts[k];
+          load[parts[k]] += weight(idx[k]);
+        }
+      }
+    }
+
     auto loads_of = [&](const std::vector<int32_t>& a) {
       std::vector<int64_t> ld(P, 0);
       for (int64_t i = 0; i < n_items; ++i) ld[a[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
@@ -157,16 +190,23 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
     hp.rho_naive = dbsp_rho(ld_naive.data(), 1, P);
     hp.rho_balanced = dbsp_rho(ld_lpt.data(), 1, P);
 
-    const std::vector<int32_t>& assign = (mode == DBSP_MODE_NAIVE) ? assign_naive : assign_lpt;
-    hp.part_load = (mode == DBSP_MODE_NAIVE) ? ld_naive : ld_lpt;
+    const std::vector<int32_t>& assign =
+        (mode == DBSP_MODE_NAIVE) ? assign_naive : (mode == DBSP_MODE_ROUNDS) ? assign_rounds : assign_lpt;
+    hp.part_load = loads_of(assign);
+    hp.rho_mode = dbsp_rho(hp.part_load.data(), 1, P);
 
-    // per-partition lists in ascending item id (= ascending head, q_block, kv_begin)
+    // per-partition lists: ascending item id (= ascending head, q_block, kv_begin), or, for the
+    // round-based placement, the order of the rounds
     hp.part_ptr.assign(P + 1, 0);
     for (int64_t i = 0; i < n_items; ++i) hp.part_ptr[assign[i] + 1]++;
     for (int32_t g = 0; g < P; ++g) hp.part_ptr[g + 1] += hp.part_ptr[g];
     hp.part_items.resize(n_items);
     std::vector<int32_t> cursor(hp.part_ptr.begin(), hp.part_ptr.end() - 1);
-    for (int64_t i = 0; i < n_items; ++i) hp.part_items[cursor[assign[i]]++] = (int32_t)i;
+    if (mode == DBSP_MODE_ROUNDS) {
+      for (int32_t i : seq) hp.part_items[cursor[assign[i]]++] = i;
+    } else {
+      for (int64_t i = 0; i < n_items; ++i) hp.part_items[cursor[assign[i]]++] = (int32_t)i;
+    }
     return DBSP_OK;
   } catch (const std::bad_alloc&) {
     err = "out of host memory while planning";

@@ -95,6 +95,7 @@ def _assert_plan_equal(mask, block, P, mode, L, c0):
     assert st["nnz"] == ref["nnz"] and st["n_items"] == len(ref["items"])
     assert st["num_partitions"] == P and st["max_item_len"] == ref["max_item_len"]
     assert st["rho_naive"] == ref["rho_naive"] and st["rho_balanced"] == ref["rho_balanced"]   # bit-exact doubles
+    assert st["rho_plan"] == ref["rho_plan"]
     eq = np.testing.assert_array_equal
     eq(pl.array(B.ROW_CNT), np.array(ref["cnt"], dtype=np.int32))
     eq(pl.array(B.BLOCKS_PER_HEAD), np.array(ref["blocks_per_head"], dtype=np.int64))
@@ -115,7 +116,7 @@ def _assert_plan_equal(mask, block, P, mode, L, c0):
 def test_planner_bit_exact_on_configs(cfg):
     mask = synth.mask_for_config(cfg)
     block = synth.CONFIGS[cfg]["block"]
-    for mode in (B.MODE_BALANCED, B.MODE_NAIVE):
+    for mode in (B.MODE_BALANCED, B.MODE_NAIVE, B.MODE_ROUNDS):
         _assert_plan_equal(mask, block, 256, mode, 0, 0)
     if cfg in (1, 5):
         _assert_plan_equal(mask, block, 8, B.MODE_BALANCED, 0, 0)
@@ -131,7 +132,7 @@ def test_planner_bit_exact_random_small(seed):
     if seed % 4 == 0:
         mask[0, 0, :] = 0                      # an empty row
     for P in (1, 2, 5, 300):
-        for mode in (B.MODE_BALANCED, B.MODE_NAIVE):
+        for mode in (B.MODE_BALANCED, B.MODE_NAIVE, B.MODE_ROUNDS):
             for L, c0 in ((0, 0), (-1, 0), (3, 0), (0, 2)):
                 _assert_plan_equal(mask, 64, P, mode, L, c0)
 
@@ -140,6 +141,8 @@ def test_planner_degenerate_masks():
     _assert_plan_equal(np.zeros((2, 3, 5), dtype=np.uint8), 64, 4, B.MODE_BALANCED, 0, 0)
     _assert_plan_equal(np.ones((2, 3, 5), dtype=np.uint8), 64, 4, B.MODE_BALANCED, 0, 0)
     _assert_plan_equal(np.ones((1, 1, 9), dtype=np.uint8), 64, 4, B.MODE_NAIVE, 2, 0)
+    _assert_plan_equal(np.zeros((2, 3, 5), dtype=np.uint8), 64, 4, B.MODE_ROUNDS, 0, 0)
+    _assert_plan_equal(np.ones((3, 2, 9), dtype=np.uint8), 64, 4, B.MODE_ROUNDS, 2, 1)
     _assert_plan_equal(np.full((1, 2, 17), 255, dtype=np.uint8), 128, 1, B.MODE_BALANCED, 0, 0)   # any nonzero byte counts
 
 
@@ -147,3 +150,4 @@ def test_five_config5_steps_replan_bit_exact():
     # per-call replanning over the denoising-step sequence (first steps only, to stay quick)
     for step, mask in enumerate(synth.mask_sequence_cfg5(4)):
         _assert_plan_equal(mask, 128, 256, B.MODE_BALANCED, 0, 0)
+        _assert_plan_equal(mask, 128, 256, B.MODE_ROUNDS, 0, 0)

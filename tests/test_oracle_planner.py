@@ -59,6 +59,42 @@ def test_greedy_stable_order_by_hand():
     assert loads == [7, 7, 4]
 
 
+def test_rounds_placement_by_hand():
+    # 2 partitions; head 0 has items of weight 3, 1 (4 blocks), head 1 has 5, 4 (9 blocks).
+    # Head order by blocks, descending: 1, 0 -> sequence of item ids 2, 3, 0, 1.
+    # Round 1 (ids 2, 3): 5 -> p0, 4 -> p1.  Round 2 (ids 0, 1): partitions by load: p1 (4), p0 (5);
+    # 3 -> p1 (7), 1 -> p0 (6).
+    assign, seq = op.rounds_partition([0, 0, 1, 1], [3, 1, 5, 4], [4, 9], 2)
+    assert seq == [2, 3, 0, 1]
+    assert assign == [1, 0, 0, 1]
+    # ties: equal head counts keep head id order, equal loads keep partition index order,
+    # equal weights keep sequence order
+    assign, seq = op.rounds_partition([0, 1, 1], [2, 1, 1], [2, 2], 2)
+    assert seq == [0, 1, 2] and assign == [0, 1, 1]
+
+
+def test_rounds_spread_is_bounded_by_the_largest_item():
+    rng = np.random.default_rng(3)
+    for _ in range(40):
+        H = int(rng.integers(1, 6)); P = int(rng.integers(1, 9))
+        heads = sorted(int(h) for h in rng.integers(0, H, size=int(rng.integers(1, 60))))
+        w = [int(x) for x in rng.integers(1, 50, size=len(heads))]
+        per_head = [sum(wi for wi, h in zip(w, heads) if h == hh) for hh in range(H)]
+        assign, seq = op.rounds_partition(heads, w, per_head, P)
+        assert sorted(seq) == list(range(len(w)))
+        loads = [0] * P
+        for i, g in enumerate(assign):
+            loads[g] += w[i]
+        assert sum(loads) == sum(w)
+        # matching the k-th heaviest item with the k-th least-loaded partition never lets the
+        # spread exceed the largest weight
+        assert max(loads) - min(loads) <= max(w)
+        # at most one item per partition per round
+        for r0 in range(0, len(seq), P):
+            gs = [assign[i] for i in seq[r0:r0 + P]]
+            assert len(set(gs)) == len(gs)
+
+
 def test_rho_range_and_conventions():
     assert op.imbalance_ratio([[0, 0, 0]]) == 1.0
     assert op.imbalance_ratio([[5, 5, 5, 5]]) == 1.0
@@ -124,7 +160,7 @@ def test_make_items_split_rule():
     assert op.auto_max_item_len(56699, 256) == 55
 
 
-def _check_plan_invariants(mask, pl, overhead=0):
+def _check_plan_invariants(mask, pl, overhead=0, rounds=False):
     H, nQ, nK = mask.shape
     # counts / CSR against a direct scan
     assert pl["nnz"] == int((mask != 0).sum())
@@ -145,7 +181,8 @@ def _check_plan_invariants(mask, pl, overhead=0):
     assert sum(pl["part_load"]) == pl["nnz"]
     for g in range(pl["P"]):
         ids = pl["part_items"][pl["part_ptr"][g]:pl["part_ptr"][g + 1]]
-        assert ids == sorted(ids)
+        if not rounds:
+            assert ids == sorted(ids)
         assert sum(pl["items"][i][3] - pl["items"][i][2] for i in ids) == pl["part_load"][g]
     # split bookkeeping
     slots = [s for s in pl["item_slot"] if s >= 0]
@@ -159,9 +196,9 @@ def test_plan_invariants_random(seed):
     H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 9)), int(rng.integers(1, 12))
     mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0.1, 0.9)), seed=seed)
     for P in (1, 3, 7, 64):
-        for mode in (op.MODE_BALANCED, op.MODE_NAIVE):
+        for mode in (op.MODE_BALANCED, op.MODE_NAIVE, op.MODE_ROUNDS):
             for L in (0, -1, 2):
-                _check_plan_invariants(mask, op.plan(mask, P, mode=mode, max_item_len=L))
+                _check_plan_invariants(mask, op.plan(mask, P, mode=mode, max_item_len=L), rounds=(mode == op.MODE_ROUNDS))
 
 
 def test_plan_degenerate_masks():
@@ -182,7 +219,8 @@ def test_config_plans_balance_well():
         pl = op.plan(mask, 256)
         assert pl["rho_balanced"] <= bound
         assert pl["rho_naive"] > pl["rho_balanced"]
-        _ = pl
+        pr = op.plan(mask, 256, mode=op.MODE_ROUNDS)
+        assert pr["rho_balanced"] <= pr["rho_plan"] <= bound + 0.03
 
 
 def test_config1_plan_invariants():
