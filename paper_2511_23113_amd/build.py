@@ -13,6 +13,11 @@ LIB_PATH = os.path.join(PKG_DIR, "libdbsp.so")
 
 SOURCES = ["planner.cpp", "api.hip", "attn_fwd.hip"]
 
+# Per-file extra flags.  The attention kernels never rely on NaN propagation; without NaN
+# handling the max chains of the softmax compile to v_max3_f32.  (Host-side argument checks in
+# api.hip do test for NaN, so the flag is not global.)
+EXTRA_FLAGS = {"attn_fwd.hip": ["-fno-honor-nans"]}
+
 # Packed-FP32 VALU ops are switched off for all device code (-packed-fp32-ops removes the feature).
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -37,7 +42,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS + list(extra_flags) + inc
+        cmd = [hipcc, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS + EXTRA_FLAGS.get(src, []) + list(extra_flags) + inc
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

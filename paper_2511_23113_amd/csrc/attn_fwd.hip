@@ -85,18 +85,25 @@ __device__ __forceinline__ float sum_xor32(float x) {
   return sw.lo + sw.hi;
 }
 
-// One wave copies 64 x 16 bytes from global memory straight into LDS: lane i reads 16 bytes at
-// base + voff(i) and they land at LDS byte address lds_dst + 16*i (M0 carries lds_dst).  Inline
-// assembly keeps the copy outside the compiler's wait-count bookkeeping: the kernel waits for
-// it explicitly (s_waitcnt vmcnt(0)) right before the barrier that publishes the tile.  No
-// "memory" clobber: LDS reads of the OTHER buffer may be scheduled across the copy.
-__device__ __forceinline__ void copy16_to_lds(const unsigned char* base, uint32_t voff, uint32_t lds_dst) {
-  asm volatile(
-      "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2"
-      :
-      : "s"(lds_dst), "v"(voff), "s"(base));
+// Direct global -> LDS copies.  One global_load_lds_dwordx4 moves 64 x 16 bytes: lane i reads
+// 16 bytes at base + voff(i) + OFF and they land at LDS byte address M0 + OFF + 16*i; the
+// instruction offset applies to both sides, so the copies of one group share a base and an M0.
+// Inline assembly keeps the copies outside the compiler's wait-count bookkeeping: the kernel
+// waits for them explicitly (s_waitcnt vmcnt(0)) right before the barrier that publishes the
+// tile.  No "memory" clobber: LDS reads of the OTHER buffer may be scheduled across a copy.
+__device__ __forceinline__ void set_copy_dst(uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(lds_dst));
+}
+template <int OFF>
+__device__ __forceinline__ void copy16_to_lds(const unsigned char* base, uint32_t voff) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(base), "n"(OFF));
+}
+// copy number n (0..3) of a group: byte offset n KiB
+__device__ __forceinline__ void copy16_nth(int n, const unsigned char* base, uint32_t voff) {
+  if (n == 0) copy16_to_lds<0>(base, voff);
+  else if (n == 1) copy16_to_lds<1024>(base, voff);
+  else if (n == 2) copy16_to_lds<2048>(base, voff);
+  else copy16_to_lds<3072>(base, voff);
 }
 
 template <int BLK, int D>
@@ -116,11 +123,12 @@ struct Cfg {
   static constexpr int ROW_BYTES = D * 2;
   static constexpr int TILE_BYTES = BLK * D * 2;
   static constexpr int LOADS = (BLK * D / 8 / 64) / NW;   // 1-KiB direct-to-LDS copies per wave per tile
-  static constexpr int STEP_ROWS = NW * 64 / NCH;         // rows between consecutive copies of one wave
-  // K's swizzle has period NCH*RPL rows; if STEP_ROWS is not a multiple of it, copies alternate
-  // between SRC_VARIANTS per-lane source offsets
-  static constexpr int SRC_VARIANTS = (STEP_ROWS % (NCH * RPL) == 0) ? 1 : (NCH * RPL) / STEP_ROWS;
-  static_assert(STEP_ROWS % (4 * RPL) == 0, "V's swizzle period must divide the copy step");
+  static constexpr int CP = LOADS / U;                    // copies of each tensor per pipeline step (one group)
+  static constexpr int RPC = 64 / NCH;                    // tile rows per copy
+  // K's swizzle has period NCH*RPL rows: consecutive copies cycle through KVAR per-lane source offsets
+  static constexpr int KVAR = (NCH * RPL) / RPC;
+  static_assert((LOADS * RPC) % (NCH * RPL) == 0, "a wave's share of a tile must start on a swizzle period");
+  static_assert(RPC % (4 * RPL) == 0, "V's swizzle period must divide the rows of one copy");
   static constexpr int NKB = 2, NVB = 2;
   static constexpr int LDS_BYTES = (NKB + NVB) * TILE_BYTES;
   static constexpr int XCH_BYTES = (NKH == 1) ? 0 : NW * (QT * (DT / 2) * 16 * 64 * 4 + QT * 2 * 64 * 4);  // end-of-item exchange
@@ -148,22 +156,18 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
   const float c = p.scale_log2;
 
   // ---- per-lane constants -------------------------------------------------------------
-  // direct-to-LDS copies: copy i of this wave fills LDS chunks [(i*NW + w)*64, +64) of a tile.
-  // The LDS tile is a linear image of the global tile except for the chunk swizzle inside a
-  // row, and consecutive copies of a wave are STEP_ROWS rows apart; with STEP_ROWS a multiple
-  // of the swizzle period the per-lane source offset is the same for every copy.
-  uint32_t k_src[C::SRC_VARIANTS], v_src;
+  // direct-to-LDS copies: wave w owns the LOADS consecutive KiB [(w*LOADS + i) KiB, i < LOADS) of
+  // every tile.  The LDS tile is a linear image of the global tile except for the chunk swizzle
+  // inside a row, which is applied to the per-lane global source offset.
+  uint32_t k_src[C::KVAR], v_src;
   {
+    const int row_in = l / C::NCH, pch = l % C::NCH;     // row inside the copy, physical chunk
 #pragma unroll
-    for (int i = 0; i < C::SRC_VARIANTS; ++i) {
-      const int pc = (i * C::NW + w) * 64 + l;          // physical chunk of copy i
-      const int row = pc / C::NCH, pch = pc % C::NCH;
-      const int kch = pch ^ ((row / C::RPL) % C::NCH);
-      k_src[i] = (row - i * C::STEP_ROWS) * C::ROW_BYTES + kch * 16;
+    for (int v = 0; v < C::KVAR; ++v) {
+      const int row = v * C::RPC + row_in;                // row modulo the swizzle period
+      k_src[v] = row_in * C::ROW_BYTES + ((pch ^ ((row / C::RPL) % C::NCH)) * 16);
     }
-    const int pc = w * 64 + l;
-    const int row = pc / C::NCH, pch = pc % C::NCH;
-    v_src = row * C::ROW_BYTES + ((pch ^ (((row / C::RPL) % (C::NCH / 4)) << 2)) * 16);
+    v_src = row_in * C::ROW_BYTES + ((pch ^ (((row_in / C::RPL) % (C::NCH / 4)) << 2)) * 16);
   }
   // K operand reads: key row KW*wc + 32*unit + r, logical chunk 2*ks + g, physical chunk
   // (2*ks + g) ^ sw.  Bits 1..3 of the chunk index are ks ^ (sw >> 1), so the address of
@@ -201,23 +205,18 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
       const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k + bh * p.nK * BLK * D);
       const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v + bh * p.nK * BLK * D);
 
-      // copies [i0, i1) of one tile of this wave
-      auto copy_k = [&](int J, int buf, int i0, int i1) {
-        const unsigned char* src = kbase + (int64_t)J * C::TILE_BYTES;
+      // byte offset of this wave's share inside a tile, same in global memory and in LDS
+      const uint32_t wave_off = w * C::LOADS * 1024;
+      // K of the first block; V of block T is copied during block T's steps
 #pragma unroll
-        for (int i = i0; i < i1; ++i)
-          copy16_to_lds(src + i * C::STEP_ROWS * C::ROW_BYTES, k_src[i % C::SRC_VARIANTS],
-                        lds_base + K_OFF + buf * C::TILE_BYTES + (i * C::NW + w) * 1024);
-      };
-      auto copy_v = [&](int J, int buf, int i0, int i1) {
-        const unsigned char* src = vbase + (int64_t)J * C::TILE_BYTES;
+      for (int grp = 0; grp < C::U; ++grp) {
+        const uint32_t off = wave_off + grp * C::CP * 1024;
 #pragma unroll
-        for (int i = i0; i < i1; ++i)
-          copy16_to_lds(src + i * C::STEP_ROWS * C::ROW_BYTES, v_src,
-                        lds_base + V_OFF + buf * C::TILE_BYTES + (i * C::NW + w) * 1024);
-      };
-
-      copy_k(kv[0], 0, 0, C::LOADS);   // K of the first block; V of block T is copied during block T's steps
+        for (int n = 0; n < C::CP; ++n) {
+          if (n % 4 == 0) set_copy_dst(lds_base + K_OFF + off + n * 1024);
+          copy16_nth(n % 4, kbase + (int64_t)kv[0] * C::TILE_BYTES + off + (n / 4) * 4096, k_src[(grp * C::CP + n) % C::KVAR]);
+        }
+      }
 
       // Q^T operands of this wave's 64 queries: lane (r, g) holds q[32*qt + r][16ks + 8g .. +7]
       const int q0 = 64 * wa;
@@ -271,9 +270,22 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
         // item) and V of block Tq, split over the U steps of block Tq
         const int Jk = kv[(Tq + 1 < n_tiles) ? Tq + 1 : n_tiles - 1];
         const int Jv = kv[(Tq < n_tiles) ? Tq : n_tiles - 1];
-        const int kbuf_next = (Tq + 1) % C::NKB, vbuf_this = Tq % C::NVB;
-        constexpr int CP = C::LOADS / C::U;                  // copies of each tensor per step
-        const int cp0 = hq * CP;
+        // this step's group of copies: [HALF*CP, HALF*CP + CP) of the wave's share of each tile
+        constexpr int CP = C::CP;
+        const uint32_t grp_off = wave_off + HALF * CP * 1024;
+        const unsigned char* k_from = kbase + (int64_t)Jk * C::TILE_BYTES + grp_off;
+        const unsigned char* v_from = vbase + (int64_t)Jv * C::TILE_BYTES + grp_off;
+        const uint32_t k_to = lds_base + K_OFF + ((Tq + 1) % C::NKB) * C::TILE_BYTES + grp_off;
+        const uint32_t v_to = lds_base + V_OFF + (Tq % C::NVB) * C::TILE_BYTES + grp_off;
+        // copies are grouped in fours: one M0 write and one base per group, instruction offsets inside
+        auto copy_k = [&](int n) {
+          if (n % 4 == 0) set_copy_dst(k_to + n * 1024);
+          copy16_nth(n % 4, k_from + (n / 4) * 4096, k_src[(HALF * CP + n) % C::KVAR]);
+        };
+        auto copy_v = [&](int n) {
+          if (n % 4 == 0) set_copy_dst(v_to + n * 1024);
+          copy16_nth(n % 4, v_from + (n / 4) * 4096, v_src);
+        };
 
         // LDS operand reads of this step
         bf16x8 ka[C::KS_QK];
@@ -303,12 +315,13 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt) {
             const f32x16& sv = S[1 - PAR][qt];
-            float mx0 = fmaxf(sv[0], sv[1]), mx1 = fmaxf(sv[2], sv[3]);
-#pragma unroll
-            for (int e = 4; e < 16; e += 4) {
-              mx0 = fmaxf(mx0, fmaxf(sv[e], sv[e + 1]));
-              mx1 = fmaxf(mx1, fmaxf(sv[e + 2], sv[e + 3]));
-            }
+            // 16 scores per lane: two chains of 3-input maxima
+            float mx0 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), mx1 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);
+            mx0 = fmaxf(fmaxf(mx0, sv[6]), sv[7]);
+            mx1 = fmaxf(fmaxf(mx1, sv[8]), sv[9]);
+            mx0 = fmaxf(fmaxf(mx0, sv[10]), sv[11]);
+            mx1 = fmaxf(fmaxf(mx1, sv[12]), sv[13]);
+            mx0 = fmaxf(fmaxf(mx0, sv[14]), sv[15]);
             const float mx = max_xor32(fmaxf(mx0, mx1));
             // The running max is raised only when some query's max grew by more than
             // 2^RESCALE_LOG2 (in exp2 units); until then P may exceed 1 by at most that factor,
@@ -322,16 +335,16 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
             float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
-              float pe[8];
+              uint32_t pw[4];
 #pragma unroll
-              for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + e], c, -mc));
-              ls0 += (pe[0] + pe[1]) + (pe[2] + pe[3]);
-              ls1 += (pe[4] + pe[5]) + (pe[6] + pe[7]);
-              u32x4 pb;
-              pb.x = pack_bf16x2(pe[0], pe[1]);
-              pb.y = pack_bf16x2(pe[2], pe[3]);
-              pb.z = pack_bf16x2(pe[4], pe[5]);
-              pb.w = pack_bf16x2(pe[6], pe[7]);
+              for (int e2 = 0; e2 < 4; ++e2) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc));
+                ls0 += p0;
+                ls1 += p1;
+                pw[e2] = pack_bf16x2(p0, p1);
+              }
+              const u32x4 pb = {pw[0], pw[1], pw[2], pw[3]};
               Pb[1 - PAR][hf][qt] = as_bf16x8(pb);
             }
             l_run[qt] = l_run[qt] * alpha[qt] + (ls0 + ls1);
@@ -351,13 +364,16 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
                 oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[PAR][ks][qt], oacc[dt][qt], 0, 0, 0);
               if constexpr (QK) {   // a tile copy after every few MFMAs
                 const int n = ks * C::DT + dt;
-                if (n < CP) copy_k(Jk, kbuf_next, cp0 + n, cp0 + n + 1);
+                if (n < CP) copy_k(n);
               }
             }
           }
         }
         if constexpr (QK) {
-          if constexpr (!PV) copy_k(Jk, kbuf_next, cp0, cp0 + CP);
+          if constexpr (!PV) {
+#pragma unroll
+            for (int n = 0; n < CP; ++n) copy_k(n);
+          }
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
@@ -368,13 +384,9 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
 #pragma unroll
             for (int qt = 0; qt < C::QT; ++qt)
               S[PAR][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qt][ks], S[PAR][qt], 0, 0, 0);
-            if (ks < CP) copy_v(Jv, vbuf_this, cp0 + ks, cp0 + ks + 1);
+            if (ks < CP) copy_v(ks);
           }
-          if constexpr (C::KS_QK < CP) copy_v(Jv, vbuf_this, cp0 + C::KS_QK, cp0 + CP);
-          // The scores are consumed by VALU code in the next step: move them to arch VGPRs now.
-          // (Accumulation registers are fully booked by O^T, Q^T and the scores being accumulated.)
-#pragma unroll
-          for (int qt = 0; qt < C::QT; ++qt) asm volatile("" : "+v"(S[PAR][qt]));
+          static_assert(C::KS_QK >= CP && 2 * C::DT >= CP, "not enough MFMA slots to spread the copies over");
         }
 
         // ---- deferred accumulator rescale: after V^T P^T of unit i-2, before that of unit i-1 --
