@@ -79,8 +79,11 @@ typedef struct dbsp_plan_opts {
  * partition with the smallest accumulated weight (ties: lowest index); each partition's list
  * in ascending item order (round order for DBSP_MODE_ROUNDS); rho_s of the naive, the greedy and
  * the chosen placement (Eq. 1 with one period).
- * Unless DBSP_PLAN_HOST_ONLY is set, the arrays are then copied to the current device and
- * scratch for split rows and busy-time capture is allocated there.
+ * Unless DBSP_PLAN_HOST_ONLY is set, the arrays are then copied to the current device, next to
+ * scratch for split rows and busy-time capture.  The copy is asynchronous (a stream of the
+ * library's own, pinned staging, buffers recycled from a process-wide pool): the call returns
+ * without waiting for it, and sparse_attn_fwd makes its stream wait for the copy, so planning the
+ * next call overlaps with the device's work on the current one.
  * Errors: DBSP_EINVAL, DBSP_ENOMEM, DBSP_EHIP.  Rows with no active block are legal.
  */
 int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
@@ -146,6 +149,8 @@ int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanc
  * either may be NULL.  Synchronises `stream` before reading. */
 int dbsp_plan_busy(const dbsp_plan* plan, uint64_t* busy_ticks, uint32_t* hw_id, void* stream);
 
+/* dbsp_plan_destroy: waits (on the host) until the last sparse_attn_fwd enqueued with this plan
+ * and the plan's upload have finished, then recycles its buffers.  NULL is ignored. */
 void dbsp_plan_destroy(dbsp_plan* plan);
 
 const char* dbsp_last_error(void);

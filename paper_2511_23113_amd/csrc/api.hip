@@ -5,8 +5,10 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "dbsp.h"
 #include "fwd_params.hpp"
@@ -33,65 +35,160 @@ int fail_hip(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return fail_hip(e_, #call);   \
   } while (0)
 
+// ---- process-wide resources: upload stream, device and pinned-host buffer pools -------------
+// Plans are created and destroyed per attention call when masks are dynamic, so their buffers are
+// recycled instead of going through hipMalloc / hipFree (which synchronises the device) each time.
+struct BufferPool {
+  struct Entry { void* ptr; size_t bytes; };
+  std::vector<Entry> free_list;
+  static constexpr size_t kMaxCached = 8;
+};
+
+std::mutex g_mu;
+hipStream_t g_upload_stream = nullptr;
+BufferPool g_dev_pool, g_pin_pool;
+
+hipError_t pool_get(BufferPool& pool, bool pinned, size_t bytes, void** out, size_t* cap) {
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    int best = -1;
+    for (size_t i = 0; i < pool.free_list.size(); ++i)
+      if (pool.free_list[i].bytes >= bytes && (best < 0 || pool.free_list[i].bytes < pool.free_list[best].bytes)) best = (int)i;
+    if (best >= 0) {
+      *out = pool.free_list[best].ptr;
+      *cap = pool.free_list[best].bytes;
+      pool.free_list.erase(pool.free_list.begin() + best);
+      return hipSuccess;
+    }
+  }
+  const size_t rounded = (bytes + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);   // 1 MiB granules
+  hipError_t e = pinned ? hipHostMalloc(out, rounded, hipHostMallocDefault) : hipMalloc(out, rounded);
+  *cap = rounded;
+  return e;
+}
+
+void pool_put(BufferPool& pool, bool pinned, void* ptr, size_t bytes) {
+  if (!ptr) return;
+  void* victim = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    pool.free_list.push_back({ptr, bytes});
+    if (pool.free_list.size() > BufferPool::kMaxCached) {
+      size_t smallest = 0;
+      for (size_t i = 1; i < pool.free_list.size(); ++i)
+        if (pool.free_list[i].bytes < pool.free_list[smallest].bytes) smallest = i;
+      victim = pool.free_list[smallest].ptr;
+      pool.free_list.erase(pool.free_list.begin() + smallest);
+    }
+  }
+  if (victim) (void)(pinned ? hipHostFree(victim) : hipFree(victim));
+}
+
+hipError_t upload_stream(hipStream_t* out) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_upload_stream) {
+    hipError_t e = hipStreamCreateWithFlags(&g_upload_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) return e;
+  }
+  *out = g_upload_stream;
+  return hipSuccess;
+}
+
+// Waits until nothing on the device still uses the plan's buffers, then recycles them.
 void free_device(dbsp_device_plan& d) {
-  if (d.blob) (void)hipFree(d.blob);
-  if (d.busy) (void)hipFree(d.busy);
-  if (d.hw_id) (void)hipFree(d.hw_id);
-  if (d.part_o) (void)hipFree(d.part_o);
-  if (d.part_lse) (void)hipFree(d.part_lse);
+  if (d.last_use && d.used) (void)hipEventSynchronize(static_cast<hipEvent_t>(d.last_use));
+  if (d.uploaded) (void)hipEventSynchronize(static_cast<hipEvent_t>(d.uploaded));
+  if (d.last_use) (void)hipEventDestroy(static_cast<hipEvent_t>(d.last_use));
+  if (d.uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.uploaded));
+  pool_put(g_dev_pool, false, d.blob, d.blob_bytes);
+  pool_put(g_pin_pool, true, d.staging, d.staging_bytes);
+  if (d.big_scratch) (void)hipFree(d.big_scratch);
+  (void)hipGetLastError();
   d = dbsp_device_plan();
 }
 
-// Grows the split-row scratch so that it holds `batches` batch entries at head dim `d`.
+// Makes sure the split-row scratch holds `batches` batch entries at head dim `d`.
 int ensure_scratch(const dbsp_plan* plan, int32_t batches, int32_t d) {
   dbsp_device_plan& dv = plan->dev;
   const dbsp_host_plan& hp = plan->host;
   if (hp.n_slots == 0) return DBSP_OK;
-  if (dv.part_o && (int64_t)dv.ws_batches * dv.ws_d >= (int64_t)batches * d) return DBSP_OK;
-  if (dv.part_o) { (void)hipFree(dv.part_o); dv.part_o = nullptr; }
-  if (dv.part_lse) { (void)hipFree(dv.part_lse); dv.part_lse = nullptr; }
-  const size_t rows = (size_t)batches * hp.n_slots * hp.block;
-  hipError_t e = hipMalloc(&dv.part_o, rows * d * sizeof(float));
-  if (e == hipSuccess) e = hipMalloc(&dv.part_lse, rows * sizeof(float));
+  const int64_t rows = (int64_t)batches * hp.n_slots * hp.block;
+  if (rows * d <= dv.scratch_floats && rows <= dv.scratch_rows) return DBSP_OK;
+  // rare: batch > 1.  The old scratch may still be in use by an earlier launch on this plan.
+  if (dv.used) (void)hipEventSynchronize(static_cast<hipEvent_t>(dv.last_use));
+  if (dv.big_scratch) { (void)hipFree(dv.big_scratch); dv.big_scratch = nullptr; }
+  hipError_t e = hipMalloc(&dv.big_scratch, (size_t)(rows * d + rows) * sizeof(float));
   if (e != hipSuccess) {
-    if (dv.part_o) { (void)hipFree(dv.part_o); dv.part_o = nullptr; }
-    dv.ws_batches = dv.ws_d = 0;
     (void)hipGetLastError();
+    dv.scratch_floats = dv.scratch_rows = 0;
     return fail(DBSP_ENOMEM, std::string("split-row scratch: ") + hipGetErrorString(e));
   }
-  dv.ws_batches = batches;
-  dv.ws_d = d;
+  dv.part_o = dv.big_scratch;
+  dv.part_lse = dv.big_scratch + rows * d;
+  dv.scratch_floats = rows * d;
+  dv.scratch_rows = rows;
   return DBSP_OK;
 }
 
+// Copies the plan to the device: one pinned staging buffer, one asynchronous copy on the
+// library's upload stream, one event that forward launches wait for.  The host does not wait.
 int upload(dbsp_plan* plan) {
   dbsp_host_plan& hp = plan->host;
   dbsp_device_plan& dv = plan->dev;
   DBSP_HIP(hipGetDevice(&dv.device));
   const std::vector<int32_t>* arrays[] = {&hp.row_ptr,    &hp.kv_idx,     &hp.items,    &hp.item_slot,
                                           &hp.split_rows, &hp.empty_rows, &hp.part_ptr, &hp.part_items};
-  size_t off[9];
+  size_t off[9];   // in int32 units, each array 16-byte aligned
   off[0] = 0;
-  for (int i = 0; i < 8; ++i) off[i + 1] = off[i] + ((arrays[i]->size() + 3) & ~size_t(3));  // keep 16-byte alignment
-  std::vector<int32_t> staging(off[8] ? off[8] : 4, 0);
+  for (int i = 0; i < 8; ++i) off[i + 1] = off[i] + ((arrays[i]->size() + 3) & ~size_t(3));
+  const size_t ints_bytes = off[8] * sizeof(int32_t);
+  const size_t busy_off = (ints_bytes + 255) & ~size_t(255);
+  const size_t hw_off = busy_off + (((size_t)hp.P * sizeof(uint64_t) + 255) & ~size_t(255));
+  const size_t up_bytes = hw_off + (((size_t)hp.P * sizeof(uint32_t) + 255) & ~size_t(255));   // uploaded part ends here
+  const int64_t rows = (int64_t)hp.n_slots * hp.block;    // scratch for one batch entry at d = 128
+  const size_t lse_off = up_bytes;
+  const size_t po_off = lse_off + (((size_t)rows * sizeof(float) + 255) & ~size_t(255));
+  const size_t total = po_off + (size_t)rows * 128 * sizeof(float);
+
+  void* blob = nullptr;
+  hipError_t e = pool_get(g_dev_pool, false, total, &blob, &dv.blob_bytes);
+  if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan device buffer: ") + hipGetErrorString(e)); }
+  dv.blob = static_cast<unsigned char*>(blob);
+  e = pool_get(g_pin_pool, true, up_bytes, &dv.staging, &dv.staging_bytes);
+  if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan staging buffer: ") + hipGetErrorString(e)); }
+
+  unsigned char* st = static_cast<unsigned char*>(dv.staging);
   for (int i = 0; i < 8; ++i)
-    if (!arrays[i]->empty()) std::memcpy(staging.data() + off[i], arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
-  DBSP_HIP(hipMalloc(&dv.blob, staging.size() * sizeof(int32_t)));
-  DBSP_HIP(hipMemcpy(dv.blob, staging.data(), staging.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-  dv.row_ptr = dv.blob + off[0];
-  dv.kv_idx = dv.blob + off[1];
-  dv.items = dv.blob + off[2];
-  dv.item_slot = dv.blob + off[3];
-  dv.split_rows = dv.blob + off[4];
-  dv.empty_rows = dv.blob + off[5];
-  dv.part_ptr = dv.blob + off[6];
-  dv.part_items = dv.blob + off[7];
-  DBSP_HIP(hipMalloc(&dv.busy, hp.P * sizeof(uint64_t)));
-  DBSP_HIP(hipMalloc(&dv.hw_id, hp.P * sizeof(uint32_t)));
-  DBSP_HIP(hipMemset(dv.busy, 0, hp.P * sizeof(uint64_t)));
-  DBSP_HIP(hipMemset(dv.hw_id, 0, hp.P * sizeof(uint32_t)));
+    if (!arrays[i]->empty()) std::memcpy(st + off[i] * sizeof(int32_t), arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
+  std::memset(st + busy_off, 0, up_bytes - busy_off);   // busy ticks and hardware ids start at zero
+
+  hipEvent_t ev_up, ev_use;
+  DBSP_HIP(hipEventCreateWithFlags(&ev_up, hipEventDisableTiming));
+  dv.uploaded = ev_up;
+  DBSP_HIP(hipEventCreateWithFlags(&ev_use, hipEventDisableTiming));
+  dv.last_use = ev_use;
+  hipStream_t us;
+  DBSP_HIP(upload_stream(&us));
+  DBSP_HIP(hipMemcpyAsync(dv.blob, st, up_bytes, hipMemcpyHostToDevice, us));
+  DBSP_HIP(hipEventRecord(ev_up, us));
+
+  const int32_t* ints = reinterpret_cast<const int32_t*>(dv.blob);
+  dv.row_ptr = ints + off[0];
+  dv.kv_idx = ints + off[1];
+  dv.items = ints + off[2];
+  dv.item_slot = ints + off[3];
+  dv.split_rows = ints + off[4];
+  dv.empty_rows = ints + off[5];
+  dv.part_ptr = ints + off[6];
+  dv.part_items = ints + off[7];
+  dv.busy = reinterpret_cast<uint64_t*>(dv.blob + busy_off);
+  dv.hw_id = reinterpret_cast<uint32_t*>(dv.blob + hw_off);
+  dv.part_lse = reinterpret_cast<float*>(dv.blob + lse_off);
+  dv.part_o = reinterpret_cast<float*>(dv.blob + po_off);
+  dv.scratch_rows = rows;
+  dv.scratch_floats = rows * 128;
   dv.resident = true;
-  return ensure_scratch(plan, 1, 128);
+  return DBSP_OK;
 }
 
 }  // namespace
@@ -197,8 +294,12 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
   p.n_empty = (int32_t)hp.empty_rows.size();
   p.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)d);
   p.scale_log2 = p.scale * 1.4426950408889634f;
-  hipError_t e = dbsp_launch_fwd(p, hp.block, d, hp.P, static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DBSP_HIP(hipStreamWaitEvent(st, static_cast<hipEvent_t>(dv.uploaded), 0));   // the plan's upload is asynchronous
+  hipError_t e = dbsp_launch_fwd(p, hp.block, d, hp.P, st);
   if (e != hipSuccess) return fail_hip(e, "sparse_attn_fwd launch");
+  DBSP_HIP(hipEventRecord(static_cast<hipEvent_t>(dv.last_use), st));
+  plan->dev.used = true;
   return DBSP_OK;
 }
 

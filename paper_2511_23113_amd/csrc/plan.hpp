@@ -27,11 +27,19 @@ struct dbsp_host_plan {
   int64_t n_items() const { return (int64_t)item_slot.size(); }
 };
 
-// Device mirror: one allocation holding every int32 array, plus scratch.
+// Device mirror.  One pooled allocation (`blob`) holds the int32 arrays, the busy-time capture
+// buffers and the split-row scratch for one batch entry at d = 128; a larger batch gets a
+// separate scratch allocation on first use.
 struct dbsp_device_plan {
   bool resident = false;
   int device = -1;
-  int32_t* blob = nullptr;  // all int32 arrays back to back
+  unsigned char* blob = nullptr;
+  size_t blob_bytes = 0;          // capacity as handed out by the pool
+  void* staging = nullptr;        // pinned host copy of the uploaded part; lives as long as the plan
+  size_t staging_bytes = 0;
+  void* uploaded = nullptr;       // hipEvent_t: the upload has finished
+  void* last_use = nullptr;       // hipEvent_t: recorded after every forward launch
+  bool used = false;
   const int32_t* row_ptr = nullptr;
   const int32_t* kv_idx = nullptr;
   const int32_t* items = nullptr;
@@ -40,11 +48,13 @@ struct dbsp_device_plan {
   const int32_t* empty_rows = nullptr;
   const int32_t* part_ptr = nullptr;
   const int32_t* part_items = nullptr;
-  uint64_t* busy = nullptr;     // [P]
-  uint32_t* hw_id = nullptr;    // [P]
-  float* part_o = nullptr;      // split-row partial outputs, f32 [ws_batches][n_slots][block][ws_d]
-  float* part_lse = nullptr;    // f32 [ws_batches][n_slots][block]
-  int32_t ws_batches = 0, ws_d = 0;
+  uint64_t* busy = nullptr;       // [P]
+  uint32_t* hw_id = nullptr;      // [P]
+  float* part_o = nullptr;        // split-row partial outputs, f32 [batches][n_slots][block][d]
+  float* part_lse = nullptr;      // f32 [batches][n_slots][block]
+  float* big_scratch = nullptr;   // separate allocation when the in-blob scratch is too small
+  int64_t scratch_floats = 0;     // capacity of part_o in floats
+  int64_t scratch_rows = 0;       // capacity of part_lse in floats
 };
 
 struct dbsp_plan {

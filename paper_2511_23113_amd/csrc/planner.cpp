@@ -14,20 +14,39 @@
 
 namespace {
 
-// Append the ascending indices of the nonzero bytes of row[0..n) to `out`; returns how many.
-inline int32_t compact_row(const uint8_t* row, int32_t n, std::vector<int32_t>& out) {
-  const size_t before = out.size();
+// Bit 7 of every byte of the result is set exactly where the byte of w is nonzero.
+inline uint64_t nonzero_bytes(uint64_t w) {
+  const uint64_t low7 = 0x7f7f7f7f7f7f7f7fULL;
+  return (((w & low7) + low7) | w) & ~low7;
+}
+
+// Number of nonzero bytes of row[0..n).
+inline int32_t count_row(const uint8_t* row, int32_t n) {
+  int32_t c = 0, j = 0;
+  for (; j + 8 <= n; j += 8) {
+    uint64_t w;
+    std::memcpy(&w, row + j, 8);
+    c += __builtin_popcountll(nonzero_bytes(w));
+  }
+  for (; j < n; ++j) c += row[j] != 0;
+  return c;
+}
+
+// Writes the ascending indices of the nonzero bytes of row[0..n) to out; returns one past the last.
+inline int32_t* compact_row(const uint8_t* row, int32_t n, int32_t* out) {
   int32_t j = 0;
   for (; j + 8 <= n; j += 8) {
     uint64_t w;
     std::memcpy(&w, row + j, 8);
-    if (w == 0) continue;
-    for (int32_t t = 0; t < 8; ++t)
-      if (row[j + t]) out.push_back(j + t);
+    uint64_t t = nonzero_bytes(w);
+    while (t) {
+      *out++ = j + (__builtin_ctzll(t) >> 3);   // little-endian: byte k of w is row[j + k]
+      t &= t - 1;
+    }
   }
   for (; j < n; ++j)
-    if (row[j]) out.push_back(j);
-  return (int32_t)(out.size() - before);
+    if (row[j]) *out++ = j;
+  return out;
 }
 
 // Binary min-heap over partitions keyed by (load, index): the root is the least-loaded
@@ -82,20 +101,28 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
     hp.H = H; hp.nQ = nQ; hp.nK = nK; hp.block = block;
     hp.P = P; hp.mode = mode; hp.item_overhead = item_overhead;
 
-    // counts + compaction in one pass over the mask
+    // pass 1: per-row counts (Alg. 1's get_blocks_per_head, kept per row), row offsets
     hp.row_cnt.resize(R);
     hp.row_ptr.resize(R + 1);
     hp.blocks_per_head.assign(H, 0);
-    hp.kv_idx.clear();
     hp.row_ptr[0] = 0;
+    int64_t total = 0;
     for (int64_t r = 0; r < R; ++r) {
-      const int32_t c = compact_row(mask + r * nK, nK, hp.kv_idx);
-      if (hp.kv_idx.size() > (size_t)INT32_MAX) { err = "more than 2^31-1 active blocks"; return DBSP_EINVAL; }
+      const int32_t c = count_row(mask + r * nK, nK);
+      total += c;
+      if (total > (int64_t)INT32_MAX) { err = "more than 2^31-1 active blocks"; return DBSP_EINVAL; }
       hp.row_cnt[r] = c;
-      hp.row_ptr[r + 1] = (int32_t)hp.kv_idx.size();
+      hp.row_ptr[r + 1] = (int32_t)total;
       hp.blocks_per_head[r / nQ] += c;
     }
-    hp.nnz = (int64_t)hp.kv_idx.size();
+    hp.nnz = total;
+    // pass 2: ascending KV block ids of every row
+    hp.kv_idx.resize(total);
+    {
+      int32_t* out = hp.kv_idx.data();
+      for (int64_t r = 0; r < R; ++r)
+        if (hp.row_cnt[r]) out = compact_row(mask + r * nK, nK, out);
+    }
 
     // split threshold
     int32_t L = max_item_len;
@@ -104,6 +131,7 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
 
     // items in row-major order
     hp.items.clear(); hp.item_slot.clear(); hp.split_rows.clear(); hp.empty_rows.clear();
+    hp.items.reserve(4 * (R + 64)); hp.item_slot.reserve(R + 64);
     hp.n_slots = 0;
     for (int64_t r = 0; r < R; ++r) {
       const int32_t c = hp.row_cnt[r];
