@@ -23,6 +23,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
 
+# HBM-side bytes per launch of dbsp_fwd_kernel (rounds placement), from rocprofv3 --pmc runs of this
+# command: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy
+# (see profiles/dbsp_fwd_kernel_wan480p_pmc.md).  Keyed by workload config; null when not measured.
+MEASURED_TRAFFIC = {3: 24.1e9}
+
 
 def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
     """The oracle as it stands, timed on this host on a bounded, seeded sample of rows."""
@@ -69,6 +74,11 @@ def main():
     ap.add_argument("--reuse-plan", action="store_true", help="static-mask mode: plan once outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--compare-placements", action="store_true",
+                    help="also time the kernel under the naive and the greedy longest-first placement (extra launches)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (3x), so that a rocprofv3 --pmc run of this "
+                         "command can scale FETCH_SIZE / WRITE_SIZE by what they read for a copy of known size")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (one GPU's share of the workload "
@@ -106,24 +116,27 @@ def main():
         vals = np.array(list(percu.values()), dtype=np.float64)
         return float(vals.max() / vals.mean()) if vals.sum() > 0 else 1.0, len(percu)
 
-    # side measurement (untimed region), kernel only: naive placement, greedy longest-first
-    # (the paper's rule, "balanced") and its round-based variant ("rounds", the one timed below)
+    # placements: planned rho_s (Eq. 1 on block counts) of the naive, the greedy longest-first and the
+    # round-based placement come from the planner alone; kernel times and busy-time imbalance of all
+    # three need extra launches of the same kernel and are only taken with --compare-placements, so
+    # that a profile of the default command sees one kind of launch only.
     side = {}
-    for name, mode in (("naive", dbsp.MODE_NAIVE), ("balanced", dbsp.MODE_BALANCED), ("rounds", dbsp.MODE_ROUNDS)):
-        plan = one_plan(mode)
-        for _ in range(2):
-            dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
-            dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
-        e1.record()
-        torch.cuda.synchronize()
-        rho_meas, n_cu = measured_rho(plan)
-        st = plan.stats()
-        side[name] = dict(kernel_ms=e0.elapsed_time(e1) / 3, rho_blocks=st["rho_plan"], rho_busy_per_cu=rho_meas, cus_seen=n_cu)
-        plan.close()
+    if args.compare_placements:
+        for name, mode in (("naive", dbsp.MODE_NAIVE), ("balanced", dbsp.MODE_BALANCED), ("rounds", dbsp.MODE_ROUNDS)):
+            plan = one_plan(mode)
+            for _ in range(2):
+                dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+            e1.record()
+            torch.cuda.synchronize()
+            rho_meas, n_cu = measured_rho(plan)
+            st = plan.stats()
+            side[name] = dict(kernel_ms=e0.elapsed_time(e1) / 3, rho_blocks=st["rho_plan"], rho_busy_per_cu=rho_meas, cus_seen=n_cu)
+            plan.close()
 
     # timed region: K steps of plan + forward
     plans = []
@@ -155,10 +168,22 @@ def main():
     total_s = t1 - t0
     kern_ms = [a.elapsed_time(b) for a, b in ev]
     kern_avg = float(np.mean(kern_ms))
+    last = static_plan if static_plan is not None else plans[-1]
+    rho_busy, cus_seen = measured_rho(last)       # busy time per compute unit in the last timed launch
+    hst = last.stats()
+    planned = {"naive": hst["rho_naive"], "balanced": hst["rho_balanced"], "rounds": hst["rho_plan"]}
     for p in plans:
         p.close()
     if static_plan is not None:
         static_plan.close()
+
+    if args.traffic_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     value = flops * args.steps / total_s / 1e12
     kern_tflops = flops / (kern_avg * 1e-3) / 1e12
@@ -178,17 +203,16 @@ def main():
         "config": {"workload": f"config {cfg}: {c['name']} B={B} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={d} block={block}, "
                                f"nnz={nnz} active blocks (density {nnz / mask.size:.3f})",
                    "step": "plan_sparse_attn + sparse_attn_fwd" if static_plan is None else "sparse_attn_fwd (plan reused)",
-                   "partitions": "one per compute unit" if args.partitions == 0 else args.partitions, "placement": "rounds"},
+                   "partitions": hst["num_partitions"], "placement": "rounds"},
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "kernel_ms": kern_avg,
         "kernel_ms_min": float(np.min(kern_ms)),
         "plan_ms": float(np.mean(plan_us)) / 1e3 if plan_us else None,
         "plan_pct_of_kernel": (float(np.mean(plan_us)) / 1e3 / kern_avg * 100.0) if plan_us else None,
-        "imbalance": side,
-        "speedup_balanced_over_naive": side["naive"]["kernel_ms"] / side["balanced"]["kernel_ms"],
-        "speedup_rounds_over_naive": side["naive"]["kernel_ms"] / side["rounds"]["kernel_ms"],
+        "imbalance": {"rho_s_planned": planned, "rho_busy_per_cu": rho_busy, "cus_seen": cus_seen,
+                      "placement_timed": "rounds", **({"compare": side} if side else {})},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg),
                      "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops},
     }
     if not args.no_cpu_baseline:
