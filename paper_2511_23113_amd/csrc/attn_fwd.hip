@@ -27,7 +27,9 @@
 //   so matrix and vector pipes run side by side; S and P are double buffered in registers.
 // Data movement:
 //   * K and V blocks go L2 -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
-//     VGPR staging), double buffered and issued a few at a time between MFMAs.
+//     VGPR staging), double buffered; each step issues one group of copies per tensor, behind
+//     MFMAs that are already queued (every inline-asm statement is a scheduling boundary for the
+//     compiler, so few groups beat many single copies).
 //   * LDS tiles are unpadded; 16-byte chunks are XOR-swizzled inside each row instead (the
 //     permutation is applied to the per-lane global source address, the LDS side of the copy
 //     is linear): K by the row index so that the 16-byte operand reads of 16 lanes (16
@@ -73,7 +75,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast
 struct halves { float lo, hi; };
 __device__ __forceinline__ halves swap_halves(float x) {
   float a = x, b = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
   return {a, b};
 }
 __device__ __forceinline__ float max_xor32(float x) {
@@ -362,9 +364,11 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
 #pragma unroll
               for (int qt = 0; qt < C::QT; ++qt)
                 oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[PAR][ks][qt], oacc[dt][qt], 0, 0, 0);
-              if constexpr (QK) {   // a tile copy after every few MFMAs
-                const int n = ks * C::DT + dt;
-                if (n < CP) copy_k(n);
+              if constexpr (QK) {   // this step's K copies, as one group behind the first MFMAs
+                if (ks == 0 && dt == 1) {
+#pragma unroll
+                  for (int n = 0; n < CP; ++n) copy_k(n);
+                }
               }
             }
           }
@@ -384,7 +388,10 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
 #pragma unroll
             for (int qt = 0; qt < C::QT; ++qt)
               S[PAR][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qt][ks], S[PAR][qt], 0, 0, 0);
-            if (ks < CP) copy_v(ks);
+            if (ks == 1) {   // this step's V copies, as one group behind the first MFMAs
+#pragma unroll
+              for (int n = 0; n < CP; ++n) copy_v(n);
+            }
           }
           static_assert(C::KS_QK >= CP && 2 * C::DT >= CP, "not enough MFMA slots to spread the copies over");
         }
