@@ -90,6 +90,27 @@ int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
                      const dbsp_plan_opts* opts, dbsp_plan** out_plan);
 
 /*
+ * plan_sparse_attn_reuse -- plan for the next mask of a sequence (denoising steps), keeping the
+ * previous plan's placement when it is still balanced enough (paper: Methodology, "Head-level
+ * Partitioning", overhead mitigation: the plan of the last step is reused if the current rho_s
+ * falls below a threshold P_s; Alg. 1 re-plans only if rho_s > P_s).
+ *
+ * previous: a plan of the same geometry (H, nQ, nK, block are taken from it) and partition count.
+ * mask_host: host, uint8 [H, nQ, nK], the new mask.  opts as for plan_sparse_attn
+ * (num_partitions 0 = the previous plan's).  reuse_threshold: P_s >= 1.
+ * Counts, index lists and items are always rebuilt for the new mask.  Its rho_s under the previous
+ * placement is evaluated by carrying the placement over per (row, chunk index); items the
+ * previous plan did not have go, in item order, to the least-loaded partition.  If that rho_s
+ * <= P_s the carried-over placement is used (*reused = 1), else the mask is planned afresh in
+ * opts->mode (*reused = 0).  *rho_under_previous receives the evaluated rho_s.  The new plan is
+ * independent of `previous`, which may be destroyed afterwards.  reused / rho_under_previous may
+ * be NULL.  Errors: DBSP_EINVAL, DBSP_ESHAPE (geometry or partition count differ), DBSP_ENOMEM, DBSP_EHIP.
+ */
+int plan_sparse_attn_reuse(const dbsp_plan* previous, const uint8_t* mask_host, const dbsp_plan_opts* opts,
+                           double reuse_threshold, dbsp_plan** out_plan, int32_t* reused,
+                           double* rho_under_previous);
+
+/*
  * sparse_attn_fwd -- block-sparse attention forward over a plan's work list.
  *
  * q:   device, bf16 [B, H, Nq, d] contiguous (d fastest);  k, v: device, bf16 [B, H, Nk, d].

@@ -181,8 +181,51 @@ def ring_work_matrix(chunk_blocks):
     return [[int(chunk_blocks[g][(i + g) % G]) for g in range(G)] for i in range(G)]
 
 
-def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0):
-    """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly)."""
+def carry_over_partition(previous, items, nQ: int, P: int):
+    """Placement of `items` taken from a previous plan (paper: Methodology, "Head-level
+    Partitioning", overhead mitigation -- the last step's plan is kept while rho_s stays under
+    a threshold P_s; Alg. 1, first test).
+
+    The paper carries a head -> GPU map over; here the unit is a work item, named by its row
+    and its ordinal among that row's items.  An item the previous plan also had keeps that
+    item's partition.  The others (a row that was empty before, or that is now cut into more
+    pieces) are taken in item order, each going to the partition with the least load in blocks
+    (lowest index on ties), after all carried-over items are in place.
+    Returns (assign, loads)."""
+    prev_part = {}
+    for g in range(P):
+        for i in previous["part_items"][previous["part_ptr"][g]:previous["part_ptr"][g + 1]]:
+            prev_part[i] = g
+    by_key = {}
+    ordinal = {}
+    for i, (h, qb, _, _) in enumerate(previous["items"]):
+        t = ordinal.get((h, qb), 0)
+        ordinal[(h, qb)] = t + 1
+        by_key[(h, qb, t)] = prev_part[i]
+    assign = [None] * len(items)
+    loads = [0] * P
+    ordinal = {}
+    for i, (h, qb, b, e) in enumerate(items):
+        t = ordinal.get((h, qb), 0)
+        ordinal[(h, qb)] = t + 1
+        g = by_key.get((h, qb, t))
+        if g is not None:
+            assign[i] = g
+            loads[g] += e - b
+    for i, (h, qb, b, e) in enumerate(items):
+        if assign[i] is None:
+            g = min(range(P), key=lambda j: (loads[j], j))
+            assign[i] = g
+            loads[g] += e - b
+    return assign, loads
+
+
+def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0,
+         previous=None, reuse_threshold: float = 1.0):
+    """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly).
+
+    With `previous` (a plan of the same geometry and P), the previous placement is kept when the
+    new mask's rho_s under it is <= reuse_threshold; `reused` and `rho_reuse` report the outcome."""
     mask = np.asarray(mask)
     H, nQ, nK = mask.shape
     cnt, per_head, total = row_counts(mask)
@@ -204,7 +247,14 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     rho_bal = imbalance_ratio([loads_of(lpt_assign)])
     rho_naive = imbalance_ratio([loads_of(nv_assign)])
     order = range(len(items))
-    if mode == MODE_BALANCED:
+    reused, rho_reuse = False, 0.0
+    if previous is not None:
+        ru_assign, ru_loads = carry_over_partition(previous, items, nQ, P)
+        rho_reuse = imbalance_ratio([ru_loads])
+        reused = rho_reuse <= reuse_threshold
+    if reused:
+        assign = ru_assign
+    elif mode == MODE_BALANCED:
         assign = lpt_assign
     elif mode == MODE_NAIVE:
         assign = nv_assign
@@ -230,4 +280,5 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
         part_ptr=part_ptr, part_items=part_items,
         part_load=loads_of(assign),
         rho_naive=rho_naive, rho_balanced=rho_bal, rho_plan=imbalance_ratio([loads_of(assign)]),
+        reused=reused, rho_reuse=rho_reuse,
     )

@@ -13,5 +13,6 @@ from .binding import (  # noqa: F401
     imbalance_ratio,
     load_library,
     plan_sparse_attn,
+    plan_sparse_attn_reuse,
     sparse_attn_fwd,
 )

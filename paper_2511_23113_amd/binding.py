@@ -22,7 +22,7 @@ ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, 
 _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 
 EXPORTS = (
-    "plan_sparse_attn", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
+    "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
     "dbsp_plan_busy", "dbsp_plan_destroy", "dbsp_last_error",
 )
 
@@ -53,6 +53,8 @@ def load_library(path: str | None = None):
     vp, i32, i64p = C.c_void_p, C.c_int32, C.POINTER(C.c_int64)
     lib.plan_sparse_attn.argtypes = [vp, i32, i32, i32, i32, C.POINTER(PlanOpts), C.POINTER(vp)]
     lib.plan_sparse_attn.restype = C.c_int
+    lib.plan_sparse_attn_reuse.argtypes = [vp, vp, C.POINTER(PlanOpts), C.c_double, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+    lib.plan_sparse_attn_reuse.restype = C.c_int
     lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
     lib.sparse_attn_fwd.restype = C.c_int
     lib.imbalance_ratio.argtypes = [vp, i32, i32, C.POINTER(C.c_double)]
@@ -142,6 +144,20 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
     return Plan(out.value, H, nQ, nK, block)
+
+
+def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,
+                           max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False):
+    """Plan the next mask of a sequence, keeping `previous`'s placement while rho_s under it stays
+    <= reuse_threshold (see dbsp.h: plan_sparse_attn_reuse).  Returns (Plan, reused, rho_under_previous)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.shape != (previous.H, previous.nQ, previous.nK):
+        raise ValueError("mask shape differs from the previous plan's")
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0)
+    out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
+    _check(load_library().plan_sparse_attn_reuse(previous.handle, mask.ctypes.data_as(C.c_void_p), C.byref(opts),
+                                                 float(reuse_threshold), C.byref(out), C.byref(reused), C.byref(rho)))
+    return Plan(out.value, previous.H, previous.nQ, previous.nK, previous.block), bool(reused.value), rho.value
 
 
 def _stream_ptr(stream):

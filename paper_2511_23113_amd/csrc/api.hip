@@ -197,21 +197,23 @@ extern "C" {
 
 const char* dbsp_last_error(void) { return g_err.c_str(); }
 
-int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
-                     const dbsp_plan_opts* opts, dbsp_plan** out_plan) {
+static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
+                     const dbsp_plan_opts* opts, const dbsp_plan* previous, double reuse_threshold,
+                     dbsp_plan** out_plan, const char* who) {
   const auto t_start = std::chrono::steady_clock::now();
   if (out_plan) *out_plan = nullptr;
-  if (!mask_host || !out_plan) return fail(DBSP_EINVAL, "plan_sparse_attn: null pointer");
-  if (H <= 0 || nQ <= 0 || nK <= 0 || block <= 0) return fail(DBSP_EINVAL, "plan_sparse_attn: H, nQ, nK and block must be positive");
-  if ((int64_t)H * nQ >= INT32_MAX) return fail(DBSP_EINVAL, "plan_sparse_attn: too many rows");
+  if (!mask_host || !out_plan) return fail(DBSP_EINVAL, std::string(who) + ": null pointer");
+  if (H <= 0 || nQ <= 0 || nK <= 0 || block <= 0) return fail(DBSP_EINVAL, std::string(who) + ": H, nQ, nK and block must be positive");
+  if ((int64_t)H * nQ >= INT32_MAX) return fail(DBSP_EINVAL, std::string(who) + ": too many rows");
   dbsp_plan_opts o;
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
   if (o.num_partitions < 0 || o.item_overhead < 0 || (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS) ||
       (o.flags & ~DBSP_PLAN_HOST_ONLY))
-    return fail(DBSP_EINVAL, "plan_sparse_attn: bad option (partitions < 0, overhead < 0, unknown mode or flag)");
+    return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, unknown mode or flag)");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
   int32_t P = o.num_partitions;
+  if (P == 0 && previous) P = previous->host.P;
   if (P == 0) {
     P = 256;
     if (!host_only) {
@@ -225,13 +227,16 @@ int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     // a 64-token block is served by a one-wave workgroup: four of them fill a compute unit
     if (block <= 64) P *= 4;
   }
+  if (previous && (previous->host.H != H || previous->host.nQ != nQ || previous->host.nK != nK || previous->host.P != P))
+    return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan has a different geometry or partition count");
   dbsp_plan* plan = new (std::nothrow) dbsp_plan();
-  if (!plan) return fail(DBSP_ENOMEM, "plan_sparse_attn: out of host memory");
+  if (!plan) return fail(DBSP_ENOMEM, std::string(who) + ": out of host memory");
   std::string err;
-  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, plan->host, err);
+  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead,
+                                previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
   if (rc != DBSP_OK) {
     delete plan;
-    return fail(rc, "plan_sparse_attn: " + err);
+    return fail(rc, std::string(who) + ": " + err);
   }
   if (!host_only) {
     rc = upload(plan);
@@ -243,6 +248,31 @@ int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   }
   plan->plan_usec = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t_start).count();
   *out_plan = plan;
+  return DBSP_OK;
+}
+
+int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
+                     const dbsp_plan_opts* opts, dbsp_plan** out_plan) {
+  return make_plan(mask_host, H, nQ, nK, block, opts, nullptr, 0.0, out_plan, "plan_sparse_attn");
+}
+
+int plan_sparse_attn_reuse(const dbsp_plan* previous, const uint8_t* mask_host, const dbsp_plan_opts* opts,
+                           double reuse_threshold, dbsp_plan** out_plan, int32_t* reused, double* rho_under_previous) {
+  if (reused) *reused = 0;
+  if (rho_under_previous) *rho_under_previous = 0.0;
+  if (!previous) {
+    if (out_plan) *out_plan = nullptr;
+    return fail(DBSP_EINVAL, "plan_sparse_attn_reuse: null previous plan");
+  }
+  if (!(reuse_threshold >= 1.0)) {
+    if (out_plan) *out_plan = nullptr;
+    return fail(DBSP_EINVAL, "plan_sparse_attn_reuse: the threshold must be at least 1");
+  }
+  const dbsp_host_plan& ph = previous->host;
+  int rc = make_plan(mask_host, ph.H, ph.nQ, ph.nK, ph.block, opts, previous, reuse_threshold, out_plan, "plan_sparse_attn_reuse");
+  if (rc != DBSP_OK) return rc;
+  if (reused) *reused = (*out_plan)->host.reused ? 1 : 0;
+  if (rho_under_previous) *rho_under_previous = (*out_plan)->host.rho_reuse;
   return DBSP_OK;
 }
 

@@ -24,6 +24,8 @@ struct dbsp_host_plan {
   std::vector<int64_t> part_load;        // [P]
   int32_t n_slots = 0;
   double rho_naive = 1.0, rho_balanced = 1.0, rho_mode = 1.0;  // rho_mode: of the placement actually used
+  bool reused = false;       // the placement was carried over from a previous plan
+  double rho_reuse = 0.0;    // rho_s of this mask under the previous plan's placement (0 if none was tried)
   int64_t n_items() const { return (int64_t)item_slot.size(); }
 };
 
@@ -64,8 +66,11 @@ struct dbsp_plan {
 };
 
 // Host planner (pure integer work, no HIP).  Returns DBSP_OK or a negative status; fills `err`.
+// `prev` (may be null) is a plan of the same geometry whose placement is kept if the new mask's
+// rho_s under it does not exceed `reuse_threshold`.
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                          int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
+                         const dbsp_host_plan* prev, double reuse_threshold,
                          dbsp_host_plan& out, std::string& err);
 
 double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions);

@@ -95,6 +95,7 @@ double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions) {
 
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                          int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
+                         const dbsp_host_plan* prev, double reuse_threshold,
                          dbsp_host_plan& hp, std::string& err) {
   try {
     const int64_t R = (int64_t)H * nQ;
@@ -153,6 +154,42 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       }
     }
     const int64_t n_items = hp.n_items();
+
+    // Plan reuse (paper: Methodology, "Head-level Partitioning", overhead mitigation; Alg. 1's
+    // first test): keep the previous step's placement while the current mask's rho_s under it
+    // stays at or below the threshold P_s.  The placement is carried over per (row, chunk index);
+    // items the previous plan did not have go, in item order, to the least-loaded partition.
+    std::vector<int32_t> assign_reuse;
+    if (prev && prev->H == H && prev->nQ == nQ && prev->nK == nK && prev->P == P) {
+      const int64_t pn = prev->n_items();
+      std::vector<int32_t> prev_part(pn), prev_first(R + 1, 0);
+      for (int32_t g = 0; g < P; ++g)
+        for (int32_t k = prev->part_ptr[g]; k < prev->part_ptr[g + 1]; ++k) prev_part[prev->part_items[k]] = g;
+      for (int64_t i = 0; i < pn; ++i) prev_first[(int64_t)prev->items[4 * i] * nQ + prev->items[4 * i + 1] + 1]++;
+      for (int64_t r = 0; r < R; ++r) prev_first[r + 1] += prev_first[r];   // prev items of row r: [prev_first[r], prev_first[r+1])
+      assign_reuse.assign(n_items, -1);
+      std::vector<int64_t> load(P, 0);
+      int64_t row_prev = -1, chunk = 0;
+      for (int64_t i = 0; i < n_items; ++i) {
+        const int64_t r = (int64_t)hp.items[4 * i] * nQ + hp.items[4 * i + 1];
+        chunk = (r == row_prev) ? chunk + 1 : 0;
+        row_prev = r;
+        if (prev_first[r] + chunk < prev_first[r + 1]) {
+          assign_reuse[i] = prev_part[prev_first[r] + chunk];
+          load[assign_reuse[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
+        }
+      }
+      for (int64_t i = 0; i < n_items; ++i) {
+        if (assign_reuse[i] >= 0) continue;
+        int32_t best = 0;
+        for (int32_t g = 1; g < P; ++g)
+          if (load[g] < load[best]) best = g;
+        assign_reuse[i] = best;
+        load[best] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
+      }
+      hp.rho_reuse = dbsp_rho(load.data(), 1, P);
+      hp.reused = hp.rho_reuse <= reuse_threshold;
+    }
 
     // naive placement: contiguous runs of ceil(n_items / P)
     std::vector<int32_t> assign_naive(n_items), assign_lpt(n_items);
@@ -218,8 +255,8 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
     hp.rho_naive = dbsp_rho(ld_naive.data(), 1, P);
     hp.rho_balanced = dbsp_rho(ld_lpt.data(), 1, P);
 
-    const std::vector<int32_t>& assign =
-        (mode == DBSP_MODE_NAIVE) ? assign_naive : (mode == DBSP_MODE_ROUNDS) ? assign_rounds : assign_lpt;
+    const std::vector<int32_t>& assign = hp.reused ? assign_reuse
+        : (mode == DBSP_MODE_NAIVE) ? assign_naive : (mode == DBSP_MODE_ROUNDS) ? assign_rounds : assign_lpt;
     hp.part_load = loads_of(assign);
     hp.rho_mode = dbsp_rho(hp.part_load.data(), 1, P);
 
@@ -230,7 +267,7 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
     for (int32_t g = 0; g < P; ++g) hp.part_ptr[g + 1] += hp.part_ptr[g];
     hp.part_items.resize(n_items);
     std::vector<int32_t> cursor(hp.part_ptr.begin(), hp.part_ptr.end() - 1);
-    if (mode == DBSP_MODE_ROUNDS) {
+    if (mode == DBSP_MODE_ROUNDS && !hp.reused) {
       for (int32_t i : seq) hp.part_items[cursor[assign[i]]++] = i;
     } else {
       for (int64_t i = 0; i < n_items; ++i) hp.part_items[cursor[assign[i]]++] = (int32_t)i;

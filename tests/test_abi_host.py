@@ -151,3 +151,80 @@ def test_five_config5_steps_replan_bit_exact():
     for step, mask in enumerate(synth.mask_sequence_cfg5(4)):
         _assert_plan_equal(mask, 128, 256, B.MODE_BALANCED, 0, 0)
         _assert_plan_equal(mask, 128, 256, B.MODE_ROUNDS, 0, 0)
+
+
+def _arrays_equal(pl, ref):
+    eq = np.testing.assert_array_equal
+    eq(pl.array(B.ROW_PTR), np.array(ref["row_ptr"], dtype=np.int32))
+    eq(pl.array(B.KV_IDX), np.array(ref["kv_idx"], dtype=np.int32))
+    eq(pl.array(B.ITEMS), np.array(ref["items"], dtype=np.int32).reshape(-1))
+    eq(pl.array(B.ITEM_SLOT), np.array(ref["item_slot"], dtype=np.int32))
+    eq(pl.array(B.PART_PTR), np.array(ref["part_ptr"], dtype=np.int32))
+    eq(pl.array(B.PART_ITEMS), np.array(ref["part_items"], dtype=np.int32))
+    eq(pl.array(B.PART_LOAD), np.array(ref["part_load"], dtype=np.int64))
+    st = pl.stats()
+    assert st["rho_plan"] == ref["rho_plan"] and st["rho_balanced"] == ref["rho_balanced"] and st["rho_naive"] == ref["rho_naive"]
+
+
+@pytest.mark.parametrize("threshold,mode", [(1.02, B.MODE_BALANCED), (1.05, B.MODE_ROUNDS), (1.10, B.MODE_BALANCED), (1.3, B.MODE_NAIVE)])
+def test_plan_reuse_over_the_config5_sequence_bit_exact(threshold, mode):
+    # chain of plans over the denoising-step masks: each step either keeps the previous placement
+    # or re-plans; decisions, rho_s values and every array must equal the oracle's chain
+    masks = list(synth.mask_sequence_cfg5(8))
+    P = 256
+    pl = B.plan_sparse_attn(masks[0], 128, num_partitions=P, mode=mode, host_only=True)
+    ref = op.plan(masks[0], P, mode=mode)
+    decisions = []
+    for mask in masks[1:]:
+        nxt, reused, rho = B.plan_sparse_attn_reuse(pl, mask, threshold, mode=mode, host_only=True)
+        ref = op.plan(mask, P, mode=mode, previous=ref, reuse_threshold=threshold)
+        assert reused == ref["reused"] and rho == ref["rho_reuse"]
+        _arrays_equal(nxt, ref)
+        pl.close()                      # the new plan does not depend on the old one
+        pl = nxt
+        decisions.append(reused)
+    pl.close()
+    if threshold >= 1.3:
+        assert all(decisions)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_plan_reuse_random_masks_bit_exact(seed):
+    # unrelated masks (many unmatched items: rows appear, vanish, split differently), small P
+    rng = np.random.default_rng(900 + seed)
+    H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(2, 12)), int(rng.integers(4, 40))
+    for P, L in ((3, 0), (7, 2), (1, 0)):
+        m0 = synth.random_mask(H, nQ, nK, float(rng.uniform(0.1, 0.9)), seed=seed)
+        pl = B.plan_sparse_attn(m0, 64, num_partitions=P, max_item_len=L, host_only=True)
+        ref = op.plan(m0, P, max_item_len=L)
+        for t in range(4):
+            m = synth.random_mask(H, nQ, nK, float(rng.uniform(0.0, 1.0)), seed=50 * seed + t)
+            thr = (1.0, 1.2, 5.0, 1.05)[t]
+            nxt, reused, rho = B.plan_sparse_attn_reuse(pl, m, thr, max_item_len=L, host_only=True)
+            ref = op.plan(m, P, max_item_len=L, previous=ref, reuse_threshold=thr)
+            assert reused == ref["reused"] and rho == ref["rho_reuse"]
+            _arrays_equal(nxt, ref)
+            pl.close()
+            pl = nxt
+        pl.close()
+
+
+def test_plan_reuse_argument_errors():
+    lib = B.load_library()
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    pl = B.plan_sparse_attn(m, 64, num_partitions=4, host_only=True)
+    out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
+    host = B.PlanOpts(0, 0, 0, 0, B.PLAN_HOST_ONLY)
+    mp = m.ctypes.data_as(C.c_void_p)
+    call = lambda prev, mask, opts, thr: lib.plan_sparse_attn_reuse(prev, mask, C.byref(opts), thr, C.byref(out), C.byref(reused), C.byref(rho))
+    assert call(None, mp, host, 1.1) == B.DBSP_EINVAL
+    assert call(pl.handle, None, host, 1.1) == B.DBSP_EINVAL
+    assert call(pl.handle, mp, host, 0.5) == B.DBSP_EINVAL
+    assert call(pl.handle, mp, host, float("nan")) == B.DBSP_EINVAL
+    assert call(pl.handle, mp, B.PlanOpts(5, 0, 0, 0, B.PLAN_HOST_ONLY), 1.1) == B.DBSP_ESHAPE
+    assert out.value is None
+    assert call(pl.handle, mp, host, 1.1) == B.DBSP_OK and reused.value == 1 and rho.value == 1.0   # P = 0: the previous plan's
+    lib.dbsp_plan_destroy(out)
+    assert lib.plan_sparse_attn_reuse(pl.handle, mp, C.byref(host), 1.1, C.byref(out), None, None) == B.DBSP_OK
+    lib.dbsp_plan_destroy(out)
+    pl.close()

@@ -196,6 +196,42 @@ def test_replanning_every_call_on_the_config5_mask_sequence():
             assert np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL, (step, h, I)
 
 
+def test_plan_reuse_chain_on_the_config5_mask_sequence():
+    # plans chained with a reuse threshold: some steps keep the previous placement (carried over
+    # per row and chunk), some re-plan; the attention result must match the oracle either way
+    import torch
+    import paper_2511_23113_amd as dbsp
+    c = synth.config_shape(5)
+    block, d = c["block"], c["d"]
+    qb, kb, vb = synth.qkv_for_config(5, c["B"], c["H"], c["Nq"], c["Nk"], d)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    o = torch.empty_like(q)
+    lse = torch.empty((c["B"], c["H"], c["Nq"]), dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(1)
+    plan, kept = None, []
+    for step, mask in enumerate(synth.mask_sequence_cfg5(8)):
+        if plan is None:
+            plan = dbsp.plan_sparse_attn(mask, block, mode=dbsp.MODE_ROUNDS)
+        else:
+            nxt, reused, rho = dbsp.plan_sparse_attn_reuse(plan, mask, 1.2, mode=dbsp.MODE_ROUNDS)
+            plan.close()
+            plan = nxt
+            kept.append(reused)
+            assert rho >= 1.0 and (plan.stats()["rho_plan"] == rho) == reused
+        dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+        rows = [(0, int(h), int(I)) for h, I in zip(rng.integers(0, c["H"], 3), rng.integers(0, c["nQ"], 3))]
+        Or, Lr = oa.masked_attention_rows(q32, k32, v32, mask, block, rows)
+        O = _host_f32(o).reshape(c["B"], c["H"], c["nQ"], block, d)
+        L = lse.cpu().numpy().reshape(c["B"], c["H"], c["nQ"], block)
+        assert np.isfinite(O).all() and np.isfinite(L).all()
+        for t, (b, h, I) in enumerate(rows):
+            assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL, (step, h, I)
+            assert np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL, (step, h, I)
+    plan.close()
+    assert any(kept) and not all(kept)          # both branches were exercised
+
+
 def test_busy_time_capture_covers_every_compute_unit():
     import paper_2511_23113_amd as dbsp
     c = synth.config_shape(5)

@@ -227,3 +227,71 @@ def test_config1_plan_invariants():
     mask = synth.mask_for_config(1)
     for P in (2, 4, 16):
         _check_plan_invariants(mask, op.plan(mask, P))
+
+
+# ---------------------------------------------------------------------------------------------
+# plan reuse under a threshold P_s (Methodology, "Head-level Partitioning", overhead mitigation)
+
+def _mask_from_counts(counts, nK):
+    H, nQ = len(counts), len(counts[0])
+    m = np.zeros((H, nQ, nK), dtype=np.uint8)
+    for h in range(H):
+        for i in range(nQ):
+            m[h, i, :counts[h][i]] = 1
+    return m
+
+
+def test_carry_over_by_hand():
+    # previous mask: rows of 4, 3, 2, 1 blocks on 2 partitions, whole rows only:
+    # longest-first greedy -> {4, 1} and {3, 2}
+    prev = op.plan(_mask_from_counts([[4, 3, 2, 1]], 8), 2, max_item_len=-1)
+    assert prev["part_load"] == [5, 5]
+    by_row = {prev["items"][i][1]: g for g in range(2) for i in prev["part_items"][prev["part_ptr"][g]:prev["part_ptr"][g + 1]]}
+    assert by_row == {0: 0, 3: 0, 1: 1, 2: 1}
+    # new mask: rows of 6, 3, 2, 1: the same placement gives loads {6+1, 3+2} = {7, 5}: rho = 7/6;
+    # a fresh greedy plan puts 6 alone and 3, 2, 1 together: {6, 6}
+    new_mask = _mask_from_counts([[6, 3, 2, 1]], 8)
+    kept = op.plan(new_mask, 2, max_item_len=-1, previous=prev, reuse_threshold=1.2)
+    assert kept["reused"] and kept["rho_reuse"] == 7 / 6 and kept["part_load"] == [7, 5]
+    assert kept["rho_plan"] == 7 / 6 and kept["rho_balanced"] == 1.0
+    fresh = op.plan(new_mask, 2, max_item_len=-1, previous=prev, reuse_threshold=1.1)
+    assert not fresh["reused"] and fresh["rho_reuse"] == 7 / 6 and fresh["part_load"] == [6, 6]
+    assert fresh["part_items"] == op.plan(new_mask, 2, max_item_len=-1)["part_items"]
+
+
+def test_carry_over_places_unmatched_items_on_the_least_loaded_partition():
+    # previous: row 1 empty -> no item for it.  New: row 1 has 6 blocks.  Carried: row 0 (2) -> g0, row 2 (1) -> g1;
+    # the new item goes to g1 (load 1 < 2): loads {2, 7}
+    prev = op.plan(_mask_from_counts([[2, 0, 1]], 8), 2, max_item_len=-1)
+    new = op.plan(_mask_from_counts([[2, 6, 1]], 8), 2, max_item_len=-1, previous=prev, reuse_threshold=10.0)
+    assert new["reused"] and new["part_load"] == [2, 7] and new["rho_reuse"] == 7 / 4.5
+    # a row cut into more pieces than before: pieces 0..k-1 follow the old ones, the rest are placed greedily
+    prev = op.plan(_mask_from_counts([[4, 1]], 8), 2, max_item_len=2)      # row 0 -> items (0..2), (2..4)
+    assert [tuple(it) for it in prev["items"]] == [(0, 0, 0, 2), (0, 0, 2, 4), (0, 1, 0, 1)]
+    new = op.plan(_mask_from_counts([[6, 1]], 8), 2, max_item_len=2, previous=prev, reuse_threshold=10.0)
+    assert len(new["items"]) == 4 and new["reused"]
+    assign, loads = op.carry_over_partition(prev, new["items"], 2, 2)
+    # greedy on 2, 2, 1 -> item0 g0, item1 g1, item2(row 1) g0;  the new third piece (2) joins g1 (load 2 < 3)
+    assert assign == [0, 1, 1, 0] and loads == [3, 4]
+
+
+def test_reuse_of_the_same_mask_reproduces_the_plan():
+    mask = synth.mask_for_config(1)
+    for mode in (op.MODE_BALANCED, op.MODE_NAIVE, op.MODE_ROUNDS):
+        a = op.plan(mask, 8, mode=mode)
+        b = op.plan(mask, 8, mode=mode, previous=a, reuse_threshold=a["rho_plan"])
+        assert b["reused"] and b["rho_reuse"] == a["rho_plan"] and b["part_load"] == a["part_load"]
+        assert [sorted(b["part_items"][b["part_ptr"][g]:b["part_ptr"][g + 1]]) for g in range(8)] == \
+               [sorted(a["part_items"][a["part_ptr"][g]:a["part_ptr"][g + 1]]) for g in range(8)]
+
+
+def test_reuse_never_exceeds_the_threshold_and_lists_stay_a_partition():
+    masks = list(synth.mask_sequence_cfg5(6))
+    ref = op.plan(masks[0], 64)
+    for m in masks[1:]:
+        ref = op.plan(m, 64, previous=ref, reuse_threshold=1.05)
+        assert sorted(ref["part_items"]) == list(range(len(ref["items"])))
+        if ref["reused"]:
+            assert ref["rho_plan"] == ref["rho_reuse"] <= 1.05
+        else:
+            assert ref["rho_reuse"] > 1.05 and ref["rho_plan"] == ref["rho_balanced"]
