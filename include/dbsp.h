@@ -135,6 +135,63 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
  */
 int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, double* rho_out);
 
+/*
+ * Planners for several GPUs (host only: every pointer below is host memory, nothing touches a
+ * GPU).  They produce the plans a U_x R_y deployment would exchange data by; one GPU cannot run
+ * that exchange, so only the plans and their rho_s are computed.  "Initial" owner of unit j of n
+ * over g groups is j / ceil(n / g), the contiguous layout sequence parallelism starts from.
+ * Sorts are stable; ties of the argmin go to the lowest index.  Optional outputs may be NULL.
+ */
+
+/*
+ * dbsp_partition_heads -- head-level partitioning over a Ulysses group of x GPUs (paper:
+ * Methodology, "Head-level Partitioning"; Alg. 1, first branch).
+ *
+ * blocks_per_head: int64 [H], dense blocks of each head (>= 0).  capacity: 0 = no limit, else
+ * the most heads one GPU may hold (capacity * x >= H).  previous_gpu_of_head: int32 [H] or
+ * NULL, the last step's plan; it is kept (*reused = 1) if rho_s of the current counts under it
+ * (*rho_previous) is <= reuse_threshold (>= 1), or if x == 1.  Otherwise heads are taken in
+ * descending count order, each going to the GPU with the least accumulated count that is not full.
+ * Out: gpu_of_head int32 [H] (required); head_list int32 [H] = head ids grouped by GPU, in
+ * placement order (ascending id when reused), list_ptr int32 [x+1]; load int64 [x];
+ * rho_contiguous = rho_s (Eq. 2) of the initial layout, rho = of the returned plan.
+ * Errors: DBSP_EINVAL.
+ */
+int dbsp_partition_heads(const int64_t* blocks_per_head, int32_t H, int32_t x, int32_t capacity,
+                         const int32_t* previous_gpu_of_head, double reuse_threshold, int32_t* gpu_of_head,
+                         int32_t* head_list, int32_t* list_ptr, int64_t* load, double* rho_contiguous,
+                         double* rho_previous, double* rho, int32_t* reused);
+
+/*
+ * dbsp_partition_blocks -- block-level partitioning for a ring of y GPUs (paper: Methodology,
+ * "Block-level Partitioning", reward factor R_b; Alg. 1, second branch).
+ *
+ * mask_host: uint8 [H, nQ, nK]; it is summed over heads.  Q blocks, in descending order of their
+ * row sums, go greedily to GPUs; KV blocks, in descending order of their column sums, go
+ * greedily to KV chunks (chunk c is processed by GPU g in iteration (c - g) mod y).  Before each
+ * argmin the load of the block's initial GPU / chunk is lowered by reward * (the block's own
+ * sum), compared in double; reward >= 0, 0 = plain greedy.  capacity_q / capacity_kv: 0 = no
+ * limit, else the most blocks per GPU / chunk.  y == 1 returns the identity plan.
+ * Out: gpu_of_q int32 [nQ], chunk_of_kv int32 [nK] (required); q_list [nQ] with q_ptr [y+1] and
+ * kv_list [nK] with kv_ptr [y+1]: ids grouped by GPU / chunk in placement order; work int64
+ * [y, y] = Eq. 3's b[i][g] under the plan (row = iteration); rho = its rho_s, rho_contiguous =
+ * rho_s of the initial layout; moved_q / moved_kv = blocks that leave their initial owner.
+ * Errors: DBSP_EINVAL, DBSP_ENOMEM.
+ */
+int dbsp_partition_blocks(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t y, double reward,
+                          int32_t capacity_q, int32_t capacity_kv, int32_t* gpu_of_q, int32_t* q_list, int32_t* q_ptr,
+                          int32_t* chunk_of_kv, int32_t* kv_list, int32_t* kv_ptr, int64_t* work,
+                          double* rho_contiguous, double* rho, int64_t* moved_q, int64_t* moved_kv);
+
+/*
+ * dbsp_ring_work -- Eq. 3's work matrix and rho_s for given maps: work[i][g] = dense blocks,
+ * over all heads, between the Q blocks of GPU g and the KV blocks of chunk (i + g) mod y.
+ * gpu_of_q int32 [nQ] / chunk_of_kv int32 [nK]: values in [0, y); NULL = the initial layout.
+ * work int64 [y, y] and rho: at least one must be given.  Errors: DBSP_EINVAL, DBSP_ENOMEM.
+ */
+int dbsp_ring_work(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t y, const int32_t* gpu_of_q,
+                   const int32_t* chunk_of_kv, int64_t* work, double* rho);
+
 /* Plan arrays (host copies, owned by the plan, valid until dbsp_plan_destroy). */
 enum dbsp_plan_array {
   DBSP_ROW_PTR = 0,         /* int32 [H*nQ + 1]  CSR offsets over rows r = h*nQ + I                  */

@@ -12,7 +12,10 @@ from .binding import (  # noqa: F401
     Plan,
     imbalance_ratio,
     load_library,
+    partition_blocks,
+    partition_heads,
     plan_sparse_attn,
     plan_sparse_attn_reuse,
+    ring_work,
     sparse_attn_fwd,
 )

@@ -24,6 +24,7 @@ _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 EXPORTS = (
     "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
     "dbsp_plan_busy", "dbsp_plan_destroy", "dbsp_last_error",
+    "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work",
 )
 
 
@@ -55,6 +56,14 @@ def load_library(path: str | None = None):
     lib.plan_sparse_attn.restype = C.c_int
     lib.plan_sparse_attn_reuse.argtypes = [vp, vp, C.POINTER(PlanOpts), C.c_double, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
     lib.plan_sparse_attn_reuse.restype = C.c_int
+    i32, i64, f64 = C.c_int32, C.c_int64, C.c_double
+    lib.dbsp_partition_heads.argtypes = [vp, i32, i32, i32, vp, f64, vp, vp, vp, vp, C.POINTER(f64), C.POINTER(f64), C.POINTER(f64), C.POINTER(i32)]
+    lib.dbsp_partition_heads.restype = C.c_int
+    lib.dbsp_partition_blocks.argtypes = [vp, i32, i32, i32, i32, f64, i32, i32, vp, vp, vp, vp, vp, vp, vp,
+                                          C.POINTER(f64), C.POINTER(f64), C.POINTER(i64), C.POINTER(i64)]
+    lib.dbsp_partition_blocks.restype = C.c_int
+    lib.dbsp_ring_work.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, C.POINTER(f64)]
+    lib.dbsp_ring_work.restype = C.c_int
     lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
     lib.sparse_attn_fwd.restype = C.c_int
     lib.imbalance_ratio.argtypes = [vp, i32, i32, C.POINTER(C.c_double)]
@@ -201,3 +210,59 @@ def imbalance_ratio(work) -> float:
     rho = C.c_double()
     _check(load_library().imbalance_ratio(w.ctypes.data_as(C.c_void_p), w.shape[0], w.shape[1], C.byref(rho)))
     return rho.value
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _split(flat, ptr):
+    return [flat[ptr[g]:ptr[g + 1]].tolist() for g in range(len(ptr) - 1)]
+
+
+def partition_heads(blocks_per_head, x: int, capacity: int = 0, previous=None, reuse_threshold: float = 1.0) -> dict:
+    """Head-level partitioning over x GPUs with plan reuse (see dbsp.h: dbsp_partition_heads)."""
+    cnt = np.ascontiguousarray(blocks_per_head, dtype=np.int64)
+    H = cnt.shape[0]
+    prev = np.ascontiguousarray(previous, dtype=np.int32) if previous is not None else None
+    if prev is not None and prev.shape != (H,):
+        raise ValueError("previous plan must hold one GPU id per head")
+    where, lst, ptr = np.empty(H, np.int32), np.empty(H, np.int32), np.empty(max(x, 0) + 1, np.int32)
+    load = np.empty(max(x, 0), np.int64)
+    rc_, rp_, r_, reused = C.c_double(), C.c_double(), C.c_double(), C.c_int32()
+    _check(load_library().dbsp_partition_heads(_ptr(cnt), H, x, capacity, _ptr(prev), float(reuse_threshold), _ptr(where), _ptr(lst),
+                                               _ptr(ptr), _ptr(load), C.byref(rc_), C.byref(rp_), C.byref(r_), C.byref(reused)))
+    return dict(gpu_of_head=where.tolist(), lists=_split(lst, ptr), loads=load.tolist(), rho_contiguous=rc_.value,
+                rho=r_.value, rho_previous=rp_.value, reused=bool(reused.value))
+
+
+def partition_blocks(mask, y: int, reward: float = 0.0, capacity_q: int = 0, capacity_kv: int = 0) -> dict:
+    """Block-level partitioning of a mask [H, nQ, nK] for a ring of y GPUs (see dbsp.h: dbsp_partition_blocks)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.ndim != 3:
+        raise ValueError("mask must be [H, nQ, nK]")
+    H, nQ, nK = mask.shape
+    yy = max(y, 0)
+    gq, ql, qp = np.empty(nQ, np.int32), np.empty(nQ, np.int32), np.empty(yy + 1, np.int32)
+    gk, kl, kp = np.empty(nK, np.int32), np.empty(nK, np.int32), np.empty(yy + 1, np.int32)
+    work = np.empty((yy, yy), np.int64)
+    rc_, r_, mq, mk = C.c_double(), C.c_double(), C.c_int64(), C.c_int64()
+    _check(load_library().dbsp_partition_blocks(_ptr(mask), H, nQ, nK, y, float(reward), capacity_q, capacity_kv, _ptr(gq), _ptr(ql),
+                                                _ptr(qp), _ptr(gk), _ptr(kl), _ptr(kp), _ptr(work), C.byref(rc_), C.byref(r_),
+                                                C.byref(mq), C.byref(mk)))
+    return dict(gpu_of_q=gq.tolist(), q_lists=_split(ql, qp), chunk_of_kv=gk.tolist(), kv_lists=_split(kl, kp),
+                work=work.tolist(), rho=r_.value, rho_contiguous=rc_.value, moved_q=mq.value, moved_kv=mk.value)
+
+
+def ring_work(mask, y: int, gpu_of_q=None, chunk_of_kv=None):
+    """Eq. 3's work matrix [iteration][GPU] and its rho_s for given maps (None = contiguous layout)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    H, nQ, nK = mask.shape
+    gq = np.ascontiguousarray(gpu_of_q, dtype=np.int32) if gpu_of_q is not None else None
+    gk = np.ascontiguousarray(chunk_of_kv, dtype=np.int32) if chunk_of_kv is not None else None
+    if (gq is not None and gq.shape != (nQ,)) or (gk is not None and gk.shape != (nK,)):
+        raise ValueError("maps must hold one id per block")
+    work = np.empty((max(y, 0), max(y, 0)), np.int64)
+    rho = C.c_double()
+    _check(load_library().dbsp_ring_work(_ptr(mask), H, nQ, nK, y, _ptr(gq), _ptr(gk), _ptr(work), C.byref(rho)))
+    return work.tolist(), rho.value

@@ -15,13 +15,17 @@
 #include "plan.hpp"
 
 namespace {
-
 thread_local std::string g_err;
+}
 
-int fail(int code, const std::string& msg) {
+int dbsp_set_error(int code, const std::string& msg) {
   g_err = msg;
   return code;
 }
+
+namespace {
+
+int fail(int code, const std::string& msg) { return dbsp_set_error(code, msg); }
 
 int fail_hip(hipError_t e, const char* what) {
   g_err = std::string(what) + ": " + hipGetErrorString(e);

@@ -74,3 +74,6 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
                          dbsp_host_plan& out, std::string& err);
 
 double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions);
+
+// Records the calling thread's error text (returned by dbsp_last_error) and hands `code` back.
+int dbsp_set_error(int code, const std::string& msg);
