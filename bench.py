@@ -79,6 +79,10 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (3x), so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE by what they read for a copy of known size")
+    ap.add_argument("--item-overhead", type=int, default=0, help="per-item cost, in blocks, the placement adds to an item's weight")
+    ap.add_argument("--fit-cost-model", action="store_true",
+                    help="also fit time = a*blocks + c*items + t0 on per-partition busy times of extra launches under several "
+                         "placements and split lengths, and compare its prediction for the timed plan with the measured kernel time")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (one GPU's share of the workload "
@@ -106,7 +110,7 @@ def main():
     flops = float(B) * nnz * 4.0 * block * block * d
 
     def one_plan(mode):
-        return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode)
+        return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead)
 
     def measured_rho(plan):
         ticks, hw = plan.busy()
@@ -137,6 +141,31 @@ def main():
             st = plan.stats()
             side[name] = dict(kernel_ms=e0.elapsed_time(e1) / 3, rho_blocks=st["rho_plan"], rho_busy_per_cu=rho_meas, cus_seen=n_cu)
             plan.close()
+
+    cost = None
+    if args.fit_cost_model:
+        # samples: one per partition and launch, all under balanced placements (the naive one runs at a
+        # different speed per block: its compute units work on different heads and miss in L2).  Block
+        # counts are spread by also planning the first half of the heads alone, item counts by the split length.
+        L = max(2, nnz // (c["H"] * c["nQ"]))          # mean row length in blocks
+        half = mask.copy()
+        half[c["H"] // 2:] = 0
+        sb, si, st_ = [], [], []
+        for m_, mode, ml in ((mask, dbsp.MODE_BALANCED, -1), (mask, dbsp.MODE_BALANCED, L // 2), (mask, dbsp.MODE_ROUNDS, L),
+                             (half, dbsp.MODE_BALANCED, -1), (half, dbsp.MODE_BALANCED, L // 2), (half, dbsp.MODE_ROUNDS, L)):
+            plan = dbsp.plan_sparse_attn(m_, block, num_partitions=args.partitions, mode=mode, max_item_len=ml)
+            for _ in range(2):
+                dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
+            ticks, _ = plan.busy()
+            sb.append(plan.array(dbsp.binding.PART_LOAD).copy())
+            si.append(np.diff(plan.array(dbsp.binding.PART_PTR)).astype(np.int64))
+            st_.append(ticks.astype(np.float64) / 100.0)            # 100 MHz ticks -> microseconds
+            plan.close()
+        sb, si, st_ = np.concatenate(sb), np.concatenate(si), np.concatenate(st_)
+        keep = si > 0
+        a_, c_, t0_, rms_ = dbsp.fit_cost_model(sb[keep], si[keep], st_[keep])
+        cost = {"a_us_per_block": a_, "c_us_per_item": c_, "t0_us": t0_, "rms_us": rms_, "samples": int(keep.sum()),
+                "item_cost_in_blocks": c_ / a_ if a_ > 0 else None, "mean_sample_us": float(st_[keep].mean())}
 
     # timed region: K steps of plan + forward
     plans = []
@@ -172,6 +201,11 @@ def main():
     rho_busy, cus_seen = measured_rho(last)       # busy time per compute unit in the last timed launch
     hst = last.stats()
     planned = {"naive": hst["rho_naive"], "balanced": hst["rho_balanced"], "rounds": hst["rho_plan"]}
+    if cost is not None:
+        pred = cost["a_us_per_block"] * last.array(dbsp.binding.PART_LOAD) + \
+            cost["c_us_per_item"] * np.diff(last.array(dbsp.binding.PART_PTR)) + cost["t0_us"]
+        cost["predicted_slowest_partition_ms"] = float(pred.max()) / 1e3
+        cost["measured_slowest_partition_ms"] = float(last.busy()[0].max()) / 100.0 / 1e3
     for p in plans:
         p.close()
     if static_plan is not None:
@@ -215,6 +249,8 @@ def main():
                      "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg),
                      "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops},
     }
+    if cost is not None:
+        out["cost_model"] = cost
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=args.cpu_budget)
     print(json.dumps(out))

@@ -136,6 +136,19 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
 int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, double* rho_out);
 
 /*
+ * dbsp_fit_cost_model -- least-squares fit of  time = a * blocks + c * items + t0  over n
+ * per-partition samples (paper: Methodology, "Sparsity-aware Strategy Selection": compute time
+ * proportional to the dense-block count plus a constant, constants fitted from profiles; the
+ * per-item term accounts for the fixed cost of starting a work item).
+ * blocks, items: host int64 [n] (PART_LOAD and the list lengths of a plan); time: host double [n]
+ * in any unit (e.g. the ticks of dbsp_plan_busy).  Out: a, c, t0 in that unit (required);
+ * rms_residual may be NULL.  Errors: DBSP_EINVAL (null pointer, n < 3, non-finite sample, or
+ * samples that do not determine the constants: blocks or items constant, or proportional).
+ */
+int dbsp_fit_cost_model(const int64_t* blocks, const int64_t* items, const double* time, int32_t n,
+                        double* a, double* c, double* t0, double* rms_residual);
+
+/*
  * Planners for several GPUs (host only: every pointer below is host memory, nothing touches a
  * GPU).  They produce the plans a U_x R_y deployment would exchange data by; one GPU cannot run
  * that exchange, so only the plans and their rho_s are computed.  "Initial" owner of unit j of n

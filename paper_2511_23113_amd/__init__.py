@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     MODE_NAIVE,
     MODE_ROUNDS,
     Plan,
+    fit_cost_model,
     imbalance_ratio,
     load_library,
     partition_blocks,

@@ -24,7 +24,7 @@ _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 EXPORTS = (
     "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
     "dbsp_plan_busy", "dbsp_plan_destroy", "dbsp_last_error",
-    "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work",
+    "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model",
 )
 
 
@@ -64,6 +64,8 @@ def load_library(path: str | None = None):
     lib.dbsp_partition_blocks.restype = C.c_int
     lib.dbsp_ring_work.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, C.POINTER(f64)]
     lib.dbsp_ring_work.restype = C.c_int
+    lib.dbsp_fit_cost_model.argtypes = [vp, vp, vp, i32, C.POINTER(f64), C.POINTER(f64), C.POINTER(f64), C.POINTER(f64)]
+    lib.dbsp_fit_cost_model.restype = C.c_int
     lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
     lib.sparse_attn_fwd.restype = C.c_int
     lib.imbalance_ratio.argtypes = [vp, i32, i32, C.POINTER(C.c_double)]
@@ -266,3 +268,15 @@ def ring_work(mask, y: int, gpu_of_q=None, chunk_of_kv=None):
     rho = C.c_double()
     _check(load_library().dbsp_ring_work(_ptr(mask), H, nQ, nK, y, _ptr(gq), _ptr(gk), _ptr(work), C.byref(rho)))
     return work.tolist(), rho.value
+
+
+def fit_cost_model(blocks, items, time):
+    """Least-squares (a, c, t0, rms residual) of time = a*blocks + c*items + t0 (see dbsp.h: dbsp_fit_cost_model)."""
+    b = np.ascontiguousarray(blocks, dtype=np.int64)
+    i = np.ascontiguousarray(items, dtype=np.int64)
+    t = np.ascontiguousarray(time, dtype=np.float64)
+    if not (b.shape == i.shape == t.shape and b.ndim == 1):
+        raise ValueError("blocks, items and time must be 1-D arrays of one length")
+    a, c, t0, rms = C.c_double(), C.c_double(), C.c_double(), C.c_double()
+    _check(load_library().dbsp_fit_cost_model(_ptr(b), _ptr(i), _ptr(t), b.shape[0], C.byref(a), C.byref(c), C.byref(t0), C.byref(rms)))
+    return a.value, c.value, t0.value, rms.value

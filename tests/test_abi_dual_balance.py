@@ -106,3 +106,29 @@ def test_argument_errors():
     assert lib.dbsp_ring_work(p(m), 1, 2, 3, 2, p(np.array([0, 2], dtype=np.int32)), None, None, C.byref(rho)) == B.DBSP_EINVAL
     # 3 KV blocks in chunks of 2 and 1: iterations cost 2 and 2 on the slowest GPU against 6 / 2
     assert lib.dbsp_ring_work(p(m), 1, 2, 3, 2, None, None, None, C.byref(rho)) == B.DBSP_OK and rho.value == 4 / 3
+
+
+def test_cost_model_fit_matches_the_oracle():
+    from oracle import cost_model as cm
+    rng = np.random.default_rng(11)
+    for trial in range(20):
+        n = int(rng.integers(3, 400))
+        b = rng.integers(100, 5000, n)
+        i = rng.integers(1, 80, n)
+        t = rng.uniform(1, 5) * b + rng.uniform(0, 100) * i + rng.uniform(0, 2000) + rng.normal(0, 30.0, n)
+        try:
+            ref = cm.fit(b, i, t)
+        except ValueError:
+            continue
+        got = B.fit_cost_model(b, i, t)
+        # same least-squares problem solved two ways (SVD there, centred normal equations here):
+        # agreement to rounding amplified by the conditioning of the design (cond < 1e5 for these ranges)
+        for g, r, scale in zip(got, ref, (1.0, 100.0, 5000.0, 30.0)):
+            assert abs(g - r) <= 1e-8 * scale, (trial, got, ref)
+    assert B.fit_cost_model([1, 3, 1], [1, 1, 2], [14.0, 18.0, 19.0])[:3] == (2.0, 5.0, 7.0)
+    lib = B.load_library()
+    for bad in (([1, 2], [1, 2], [1.0, 2.0]), ([2, 4, 6, 8], [1, 2, 3, 4], [1.0, 2.0, 3.0, 4.0]), ([5, 5, 5], [1, 2, 3], [1.0, 2.0, 3.0]),
+                ([1, 3, 1], [1, 1, 2], [1.0, float("inf"), 2.0])):
+        with pytest.raises(B.DbspError):
+            B.fit_cost_model(*bad)
+    assert b"determine" in lib.dbsp_last_error() or b"finite" in lib.dbsp_last_error()

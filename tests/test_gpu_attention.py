@@ -251,3 +251,32 @@ def test_busy_time_capture_covers_every_compute_unit():
     rho_busy = float(ticks.max() / ticks.mean())
     assert 1.0 <= rho_busy < 1.5 and st["rho_plan"] < 1.05
     plan.close()
+
+
+def test_cost_model_fitted_on_busy_times_predicts_another_plan():
+    # fit time = a*blocks + c*items + t0 on per-partition busy times of config 5 under the naive
+    # placement (spread-out loads) and two split lengths; predict the balanced plan's slowest partition
+    import paper_2511_23113_amd as dbsp
+    from paper_2511_23113_amd import binding as B
+    c = synth.config_shape(5)
+    mask = synth.mask_for_config(5)
+    qb, kb, vb = synth.qkv_for_config(5, c["B"], c["H"], c["Nq"], c["Nk"], c["d"])
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+
+    def sample(mode, L):
+        plan = dbsp.plan_sparse_attn(mask, c["block"], mode=mode, max_item_len=L)
+        for _ in range(2):
+            dbsp.sparse_attn_fwd(plan, q, k, v)
+        ticks, _ = plan.busy()
+        out = plan.array(B.PART_LOAD).copy(), np.diff(plan.array(B.PART_PTR)).astype(np.int64), ticks.astype(np.float64) / 100.0
+        plan.close()
+        return out
+
+    sets = [sample(dbsp.MODE_NAIVE, 8), sample(dbsp.MODE_NAIVE, 24), sample(dbsp.MODE_BALANCED, 12)]
+    blocks, items, usec = (np.concatenate(x) for x in zip(*sets))
+    keep = items > 0
+    a, ci, t0, rms = dbsp.fit_cost_model(blocks[keep], items[keep], usec[keep])
+    assert a > 0 and ci >= 0 and rms < 0.15 * usec[keep].mean()
+    pb, pi, pt = sample(dbsp.MODE_BALANCED, 0)
+    pred = a * pb + ci * pi + t0
+    assert abs(pred.max() - pt.max()) <= 0.15 * pt.max()
