@@ -42,6 +42,8 @@
 
 #include "fwd_params.hpp"
 
+#include <cstdlib>
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -108,16 +110,16 @@ __device__ __forceinline__ void copy16_nth(int n, const unsigned char* base, uin
   else copy16_to_lds<3072>(base, voff);
 }
 
-template <int BLK, int D>
+template <int BLK, int D, int QT_>
 struct Cfg {
-  static constexpr int NQH = BLK / 64;      // 64-query groups
+  static constexpr int NQH = BLK / (32 * QT_);   // query groups, one per wave row
   static constexpr int NKH = BLK / 64;      // 64-key groups of a KV block, one per wave column
   static constexpr int NW = NQH * NKH;      // waves
   static constexpr int NT = NW * 64;        // threads
   static constexpr int KW = BLK / NKH;      // keys per wave per KV block
   static constexpr int U = KW / 32;         // 32-key pipeline units per wave per KV block (always 2)
   static_assert(U == 2, "the pipeline below assumes two units per KV block");
-  static constexpr int QT = 2;              // 32-query tiles per wave
+  static constexpr int QT = QT_;            // 32-query tiles per wave
   static constexpr int DT = D / 32;         // 32-wide tiles of the head dim
   static constexpr int KS_QK = D / 16;      // k-steps of K Q^T
   static constexpr int NCH = D / 8;         // 16-byte chunks per row
@@ -138,14 +140,14 @@ struct Cfg {
   static_assert(DT % 2 == 0, "the head dim is split between the two key-half waves at the end of an item");
 };
 
-template <int BLK, int D>
-__global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
+template <int BLK, int D, int QT_>
+__global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
     const dbsp_fwd_params p, const int32_t* __restrict__ g_row_ptr, const int32_t* __restrict__ g_kv_idx,
     const int4* __restrict__ g_items, const int32_t* __restrict__ g_item_slot,
     const int32_t* __restrict__ g_part_ptr, const int32_t* __restrict__ g_part_items) {
   // the plan's index arrays are read-only for the whole launch: separate __restrict__ const
   // arguments let the compiler fetch them through the scalar unit
-  using C = Cfg<BLK, D>;
+  using C = Cfg<BLK, D, QT_>;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   constexpr int K_OFF = 0, V_OFF = C::NKB * C::TILE_BYTES;   // byte offsets inside the dynamic LDS block
   const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
       }
 
       // Q^T operands of this wave's 64 queries: lane (r, g) holds q[32*qt + r][16ks + 8g .. +7]
-      const int q0 = 64 * wa;
+      const int q0 = 32 * C::QT * wa;
       bf16x8 qreg[C::QT][C::KS_QK];
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt) {
@@ -230,14 +232,17 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
         for (int ks = 0; ks < C::KS_QK; ++ks)
           qreg[qt][ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 16 * ks + 8 * g));
       }
-      // Park Q in accumulation registers (the MFMA reads its B operand from there directly): the
-      // arch-VGPR file is the scarce one in the KV loop.  This also makes the compiler wait for
-      // the Q loads here, before the loop, rather than at their first use inside it (a wait
-      // inside the loop would also wait for the in-flight tile copies: same counter).
+      // Make the compiler wait for the Q loads here, before the loop, rather than at their first use
+      // inside it (a wait inside the loop would also wait for the in-flight tile copies: same
+      // counter).  With eight waves (two per SIMD, 256 registers each) nothing lives in accumulation
+      // registers: every MFMA reads and writes the arch-VGPR file and the softmax reads S in place.
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
-        for (int ks = 0; ks < C::KS_QK; ++ks) asm volatile("" : "+a"(qreg[qt][ks]));
+        for (int ks = 0; ks < C::KS_QK; ++ks) {
+          if constexpr (C::QT == 1) asm volatile("" : "+v"(qreg[qt][ks]));
+          else asm volatile("" : "+a"(qreg[qt][ks]));
+        }
 
       f32x16 oacc[C::DT][C::QT];
 #pragma unroll
@@ -255,6 +260,8 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
       f32x16 S[2][C::QT];
       bf16x8 Pb[2][2][C::QT];
 
+      int j_cur = kv[0], j_nxt = kv[(1 < n_tiles) ? 1 : 0], j_pre = kv[(2 < n_tiles) ? 2 : n_tiles - 1];
+
       // One pipeline step.  PAR = parity of the step; QK / SM / PV say which stages are live
       // (all three in the steady state; fewer while the pipeline fills and drains).
       auto step = [&](int i, auto par_tag, auto qk_tag, auto sm_tag, auto pv_tag) {
@@ -270,8 +277,14 @@ __global__ __launch_bounds__(BLK * BLK / 64) void dbsp_fwd_kernel(
         }
         // tile copies of this step: K of block Tq+1 (clamped at the end: one redundant copy per
         // item) and V of block Tq, split over the U steps of block Tq
-        const int Jk = kv[(Tq + 1 < n_tiles) ? Tq + 1 : n_tiles - 1];
-        const int Jv = kv[(Tq < n_tiles) ? Tq : n_tiles - 1];
+        // block ids come from scalar loads issued one KV block ahead (j_cur = kv[Tq], j_nxt = kv[Tq+1],
+        // clamped), so that no step waits for the scalar cache
+        if (HALF == 0 && i > 0) {
+          j_cur = j_nxt;
+          j_nxt = j_pre;
+          j_pre = kv[(Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1];
+        }
+        const int Jk = j_nxt, Jv = j_cur;
         // this step's group of copies: [HALF*CP, HALF*CP + CP) of the wave's share of each tile
         constexpr int CP = C::CP;
         const uint32_t grp_off = wave_off + HALF * CP * 1024;
@@ -584,17 +597,17 @@ __global__ __launch_bounds__(256) void dbsp_fixup_kernel(const dbsp_fwd_params p
   }
 }
 
-template <int BLK, int D>
+template <int BLK, int D, int QT_>
 hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
-  using C = Cfg<BLK, D>;
+  using C = Cfg<BLK, D, QT_>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbsp_fwd_kernel<BLK, D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbsp_fwd_kernel<BLK, D, QT_>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dbsp_fwd_kernel<BLK, D>), dim3(P), dim3(C::NT), C::LDS_BYTES, stream, p, p.row_ptr, p.kv_idx,
+  hipLaunchKernelGGL((dbsp_fwd_kernel<BLK, D, QT_>), dim3(P), dim3(C::NT), C::LDS_BYTES, stream, p, p.row_ptr, p.kv_idx,
                      reinterpret_cast<const int4*>(p.items), p.item_slot, p.part_ptr, p.part_items);
   return hipGetLastError();
 }
@@ -603,10 +616,15 @@ hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
 
 hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, int P, hipStream_t stream) {
   hipError_t e;
-  if (block == 128 && d == 128) e = launch_fwd<128, 128>(p, P, stream);
-  else if (block == 128 && d == 64) e = launch_fwd<128, 64>(p, P, stream);
-  else if (block == 64 && d == 128) e = launch_fwd<64, 128>(p, P, stream);
-  else if (block == 64 && d == 64) e = launch_fwd<64, 64>(p, P, stream);
+  // 128-token blocks: 1 = eight waves of 32 queries (two per SIMD), 2 = four waves of 64 queries
+  static const int qt128 = [] {
+    const char* s = std::getenv("DBSP_QUERY_TILES");
+    return (s && s[0] == '2') ? 2 : 1;
+  }();
+  if (block == 128 && d == 128) e = (qt128 == 1) ? launch_fwd<128, 128, 1>(p, P, stream) : launch_fwd<128, 128, 2>(p, P, stream);
+  else if (block == 128 && d == 64) e = (qt128 == 1) ? launch_fwd<128, 64, 1>(p, P, stream) : launch_fwd<128, 64, 2>(p, P, stream);
+  else if (block == 64 && d == 128) e = launch_fwd<64, 128, 2>(p, P, stream);
+  else if (block == 64 && d == 64) e = launch_fwd<64, 64, 2>(p, P, stream);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   const int fix = p.B * (p.n_split + p.n_empty);
