@@ -264,13 +264,19 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
 
       // One pipeline step.  PAR = parity of the step; QK / SM / PV say which stages are live
       // (all three in the steady state; fewer while the pipeline fills and drains).
-      auto step = [&](int i, auto par_tag, auto qk_tag, auto sm_tag, auto pv_tag) {
+      auto step = [&](int i, auto par_tag, auto qk_tag, auto sm_tag, auto pv_tag, auto buf_tag) {
         constexpr int PAR = decltype(par_tag)::value;
+        // BUF = parity of the KV block of the K Q^T stage when it is known at compile time (steady
+        // state: every LDS address is then a loop-invariant register plus an immediate), else -1
+        constexpr int BUF = decltype(buf_tag)::value;
         constexpr bool QK = decltype(qk_tag)::value, SM = decltype(sm_tag)::value, PV = decltype(pv_tag)::value;
         // with two units per KV block the step parity is also the unit's half of the block
         constexpr int HALF = (C::U == 1) ? 0 : PAR;
         const int Tq = i / C::U, hq = HALF;                  // unit of the K Q^T stage
         const int Tp = (i - 2) / C::U, hp = HALF;            // unit of the V^T P^T stage
+        static_assert(C::NKB == 2 && C::NVB == 2, "buffer parities below assume double buffering");
+        const int bq = (BUF >= 0) ? BUF : (Tq & 1);          // buffer of block Tq (K read, V copy)
+        const int bp = (BUF >= 0) ? 1 - BUF : (Tp & 1);      // buffer of block Tp = Tq - 1 (V read)
         if (C::U == 1 || PAR == 0) {
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's copies issued so far have landed
           __syncthreads();   // ... and everybody's; every wave is past the steps that read the buffers refilled next
@@ -290,8 +296,8 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
         const uint32_t grp_off = wave_off + HALF * CP * 1024;
         const unsigned char* k_from = kbase + (int64_t)Jk * C::TILE_BYTES + grp_off;
         const unsigned char* v_from = vbase + (int64_t)Jv * C::TILE_BYTES + grp_off;
-        const uint32_t k_to = lds_base + K_OFF + ((Tq + 1) % C::NKB) * C::TILE_BYTES + grp_off;
-        const uint32_t v_to = lds_base + V_OFF + (Tq % C::NVB) * C::TILE_BYTES + grp_off;
+        const uint32_t k_to = lds_base + K_OFF + (1 - bq) * C::TILE_BYTES + grp_off;
+        const uint32_t v_to = lds_base + V_OFF + bq * C::TILE_BYTES + grp_off;
         // copies are grouped in fours: one M0 write and one base per group, instruction offsets inside
         auto copy_k = [&](int n) {
           if (n % 4 == 0) set_copy_dst(k_to + n * 1024);
@@ -304,7 +310,7 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
 
         // LDS operand reads of this step
         bf16x8 ka[C::KS_QK];
-        const unsigned char* sK = lds + K_OFF + (Tq % C::NKB) * C::TILE_BYTES + hq * 32 * C::ROW_BYTES;
+        const unsigned char* sK = lds + K_OFF + bq * C::TILE_BYTES + hq * 32 * C::ROW_BYTES;
         constexpr int PF_K = C::KS_QK / 2;   // K operand reads run this many k-steps ahead of their MFMAs
         auto read_k = [&](int ks) { ka[ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(sK + (k_rd0 ^ (ks << 5)))); };
         if constexpr (QK) {
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
           for (int ks = 0; ks < PF_K; ++ks) read_k(ks);
         }
         s16x4 va[2][C::DT][2];
-        const unsigned char* sV = lds + V_OFF + (Tp % C::NVB) * C::TILE_BYTES + hp * 32 * C::ROW_BYTES;
+        const unsigned char* sV = lds + V_OFF + bp * C::TILE_BYTES + hp * 32 * C::ROW_BYTES;
         auto read_v = [&](int ks) {
 #pragma unroll
           for (int dt = 0; dt < C::DT; ++dt) {
@@ -433,14 +439,24 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
       using Yes = std::true_type;
       using No = std::false_type;
       // fill (two steps), steady state, drain (two steps); NU is even, so parities are static
-      step(0, T0{}, Yes{}, No{}, No{});
-      step(1, T1{}, Yes{}, Yes{}, No{});
-      for (int i = 2; i < NU; i += 2) {
-        step(i, T0{}, Yes{}, Yes{}, Yes{});
-        step(i + 1, T1{}, Yes{}, Yes{}, Yes{});
+      using B0 = std::integral_constant<int, 0>;
+      using B1 = std::integral_constant<int, 1>;
+      using Bx = std::integral_constant<int, -1>;
+      step(0, T0{}, Yes{}, No{}, No{}, B0{});
+      step(1, T1{}, Yes{}, Yes{}, No{}, B0{});
+      int i = 2;
+      for (; i + 2 < NU; i += 4) {           // two KV blocks per trip: odd block, then even block
+        step(i, T0{}, Yes{}, Yes{}, Yes{}, B1{});
+        step(i + 1, T1{}, Yes{}, Yes{}, Yes{}, B1{});
+        step(i + 2, T0{}, Yes{}, Yes{}, Yes{}, B0{});
+        step(i + 3, T1{}, Yes{}, Yes{}, Yes{}, B0{});
       }
-      step(NU, T0{}, No{}, Yes{}, Yes{});
-      step(NU + 1, T1{}, No{}, No{}, Yes{});
+      if (i < NU) {                          // one odd block left
+        step(i, T0{}, Yes{}, Yes{}, Yes{}, B1{});
+        step(i + 1, T1{}, Yes{}, Yes{}, Yes{}, B1{});
+      }
+      step(NU, T0{}, No{}, Yes{}, Yes{}, Bx{});
+      step(NU + 1, T1{}, No{}, No{}, Yes{}, Bx{});
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant last K copy must not outlive the item
 
       // ---- end of item: combine the key halves (if the block has two) and store ----------------
