@@ -330,45 +330,50 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
         if constexpr (PV) read_v(0);
 
         // ---- softmax of unit i-1 (VALU), reading S[1-PAR], writing Pb[1-PAR] --------------
+        // Speculative: probabilities are formed against the running max as it stands, which is
+        // right unless some score exceeds it by more than 2^RESCALE_LOG2 (in exp2 units; until
+        // then P may exceed 1 by at most that factor, which f32 / bf16 hold without loss).  The
+        // test needs no cross-lane exchange (any lane's excess sends the whole wave to the slow
+        // path below), so the common path pays neither the row-max exchange nor a rescale factor.
         bool pend = false;
-        float alpha[C::QT];
+        float l_spec[C::QT];
+        // p = exp2(s*c - mc) for the 16 scores of tile qt, packed to bf16 into Pb; returns their sum
+        auto probabilities = [&](int qt, float mc) {
+          const f32x16& sv = S[1 - PAR][qt];
+          float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            uint32_t pw[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc));
+              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc));
+              ls0 += p0;
+              ls1 += p1;
+              pw[e2] = pack_bf16x2(p0, p1);
+            }
+            const u32x4 pb = {pw[0], pw[1], pw[2], pw[3]};
+            Pb[1 - PAR][hf][qt] = as_bf16x8(pb);
+          }
+          return ls0 + ls1;
+        };
+        // largest of this lane's 16 scores of tile qt: two chains of 3-input maxima
+        auto lane_max = [&](int qt) {
+          const f32x16& sv = S[1 - PAR][qt];
+          float mx0 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), mx1 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);
+          mx0 = fmaxf(fmaxf(mx0, sv[6]), sv[7]);
+          mx1 = fmaxf(fmaxf(mx1, sv[8]), sv[9]);
+          mx0 = fmaxf(fmaxf(mx0, sv[10]), sv[11]);
+          mx1 = fmaxf(fmaxf(mx1, sv[12]), sv[13]);
+          mx0 = fmaxf(fmaxf(mx0, sv[14]), sv[15]);
+          return fmaxf(mx0, mx1);
+        };
         if constexpr (SM) {
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt) {
-            const f32x16& sv = S[1 - PAR][qt];
-            // 16 scores per lane: two chains of 3-input maxima
-            float mx0 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), mx1 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);
-            mx0 = fmaxf(fmaxf(mx0, sv[6]), sv[7]);
-            mx1 = fmaxf(fmaxf(mx1, sv[8]), sv[9]);
-            mx0 = fmaxf(fmaxf(mx0, sv[10]), sv[11]);
-            mx1 = fmaxf(fmaxf(mx1, sv[12]), sv[13]);
-            mx0 = fmaxf(fmaxf(mx0, sv[14]), sv[15]);
-            const float mx = max_xor32(fmaxf(mx0, mx1));
-            // The running max is raised only when some query's max grew by more than
-            // 2^RESCALE_LOG2 (in exp2 units); until then P may exceed 1 by at most that factor,
-            // which f32 / bf16 hold without loss, and the accumulator rescale is skipped.
-            const bool need = __builtin_amdgcn_ballot_w64((mx - m_run[qt]) * c > RESCALE_LOG2) != 0;
-            const float m_new = need ? fmaxf(m_run[qt], mx) : m_run[qt];
-            alpha[qt] = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * c);
-            pend = pend || need;
-            m_run[qt] = m_new;
-            const float mc = m_new * c;
-            float ls0 = 0.f, ls1 = 0.f;
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-              uint32_t pw[4];
-#pragma unroll
-              for (int e2 = 0; e2 < 4; ++e2) {
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc));
-                ls0 += p0;
-                ls1 += p1;
-                pw[e2] = pack_bf16x2(p0, p1);
-              }
-              const u32x4 pb = {pw[0], pw[1], pw[2], pw[3]};
-              Pb[1 - PAR][hf][qt] = as_bf16x8(pb);
-            }
-            l_run[qt] = l_run[qt] * alpha[qt] + (ls0 + ls1);
+            const float over = (lane_max(qt) - m_run[qt]) * c;
+            pend = pend || (__builtin_amdgcn_ballot_w64(over > RESCALE_LOG2) != 0);
+            l_spec[qt] = l_run[qt] + probabilities(qt, m_run[qt] * c);
           }
         }
 
@@ -415,22 +420,30 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
           static_assert(C::KS_QK >= CP && 2 * C::DT >= CP, "not enough MFMA slots to spread the copies over");
         }
 
-        // ---- deferred accumulator rescale: after V^T P^T of unit i-2, before that of unit i-1 --
+        // ---- slow path: raise the running max, redo the probabilities, rescale the accumulator
+        //      (after V^T P^T of unit i-2, before that of unit i-1) ------------------------------
         if constexpr (SM) {
-          // pin the softmax results here: otherwise the compiler sinks the exponentials below the
-          // (rarely taken) branch, out of the block whose MFMAs they are meant to overlap with
+          // pin the speculative results here: otherwise the compiler sinks the exponentials below
+          // the (rarely taken) branch, out of the block whose MFMAs they are meant to overlap with
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt) {
-            asm volatile("" ::"v"(Pb[1 - PAR][0][qt]), "v"(Pb[1 - PAR][1][qt]), "v"(l_run[qt]));
+            asm volatile("" ::"v"(Pb[1 - PAR][0][qt]), "v"(Pb[1 - PAR][1][qt]), "v"(l_spec[qt]));
           }
           if (pend) {
 #pragma unroll
-            for (int qt = 0; qt < C::QT; ++qt)
+            for (int qt = 0; qt < C::QT; ++qt) {
+              const float m_new = fmaxf(m_run[qt], max_xor32(lane_max(qt)));
+              const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * c);
+              m_run[qt] = m_new;
+              l_spec[qt] = l_run[qt] * alpha + probabilities(qt, m_new * c);
 #pragma unroll
               for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[dt][qt][e] *= alpha[qt];
+                for (int e = 0; e < 16; ++e) oacc[dt][qt][e] *= alpha;
+            }
           }
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt) l_run[qt] = l_spec[qt];
         }
       };
 
