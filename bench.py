@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
 # HBM-side bytes per launch of dbsp_fwd_kernel (rounds placement), from rocprofv3 --pmc runs of this
 # command: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy
 # (see profiles/dbsp_fwd_kernel_wan480p_pmc.md).  Keyed by workload config; null when not measured.
-MEASURED_TRAFFIC = {3: 24.1e9}
+MEASURED_TRAFFIC = {3: 16.6e9}
 
 
 def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):

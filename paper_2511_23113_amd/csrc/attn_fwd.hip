@@ -9,22 +9,31 @@
 // item costs its number of dense blocks.
 //
 // Work split inside a workgroup (wave = 64 lanes, lane = 32*g + r):
-//   * waves form a (query half) x (key half) grid: wave (a, c) owns 64 query columns and, of
-//     every KV block, the keys [c*KW, (c+1)*KW).  Each wave keeps its own running softmax
+//   * waves form a (query group) x (key half) grid: wave (a, c) owns QT tiles of 32 query columns
+//     and, of every KV block, the keys [c*KW, (c+1)*KW).  Each wave keeps its own running softmax
 //     statistics over its key half; the two key halves are combined once per item.
+//     128-token blocks run QT = 1: eight waves, two per SIMD, 256 registers each, everything in
+//     the arch-VGPR file (the MFMAs read and write it directly, the softmax reads S in place).
+//     64-token blocks run QT = 2 in a single wave (accumulators in accumulation registers).
 //   * Products are formed transposed, S^T = K Q^T and O^T = V^T P^T, with
-//     v_mfma_f32_32x32x16_bf16: lane r holds query r, so m and l are per-lane scalars, and a
-//     K (or V^T) operand read from LDS feeds two MFMAs (the wave's two 32-query tiles).
+//     v_mfma_f32_32x32x16_bf16: lane r holds query r, so m and l are per-lane scalars.
 //   * S^T's accumulator registers 8h..8h+7 of a 32-key tile hold, in lane group g, the keys
 //     16h + {4g..4g+3, 8+4g..8+4g+3}; packed to bf16 they are the B operand of the PV product
 //     for that 16-key step.  The matching V^T operand comes from two transposing LDS reads
 //     (ds_read_b64_tr_b16) of row-major V: in a group of 16 lanes, lane 4j+a supplies the
 //     address of 4 consecutive d-values of key j, and lane i receives d-value i of 4 keys.
-// Software pipeline (one wave per SIMD, so overlap has to come from one instruction stream):
-//   the unit of work is 32 keys x 64 queries.  Step i issues, as independent work,
+// Software pipeline:
+//   the unit of work is 32 keys x (32 QT) queries.  Step i issues, as independent work,
 //     the MFMAs of  K Q^T of unit i   and of  V^T P^T of unit i-2,  and
 //     the VALU work of the softmax of unit i-1,
-//   so matrix and vector pipes run side by side; S and P are double buffered in registers.
+//   so matrix and vector pipes run side by side inside one instruction stream (and across the
+//   two waves of a SIMD); S and P are double buffered in registers.  The softmax is speculative:
+//   probabilities are formed against the running max as it stands; only when a score exceeds it
+//   by more than 2^RESCALE_LOG2 is the unit redone with a raised max and the accumulator rescaled.
+//   The steady state is unrolled over two KV blocks, so LDS buffer offsets are immediates.
+// At full occupancy of the chip the kernel runs power-limited (the shader clock drops to about
+// 1.8 GHz with all 256 compute units busy, 2.4 GHz with half of them), so instructions and
+// bytes saved count as much as cycles saved.
 // Data movement:
 //   * K and V blocks go L2 -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
 //     VGPR staging), double buffered; each step issues one group of copies per tensor, behind
@@ -41,8 +50,6 @@
 #include <type_traits>
 
 #include "fwd_params.hpp"
-
-#include <cstdlib>
 
 namespace {
 
@@ -189,8 +196,12 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
     const int key = C::KW * wc + 4 * g + j;
     const int sw = ((key / C::RPL) % (C::NCH / 4)) << 2;
 #pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
-      v_rd[dt] = key * C::ROW_BYTES + ((((4 * dt) ^ sw) + 2 * hh + (a4 >> 1)) << 4) + (a4 & 1) * 8;
+    for (int dt = 0; dt < C::DT; ++dt) {
+      // V's region offset is part of the per-lane base (kept opaque), so that buffer, unit and
+      // k-step offsets of a read fit the instruction's 16-bit immediate
+      v_rd[dt] = V_OFF + key * C::ROW_BYTES + ((((4 * dt) ^ sw) + 2 * hh + (a4 >> 1)) << 4) + (a4 & 1) * 8;
+      asm volatile("" : "+v"(v_rd[dt]));
+    }
   }
 
   uint64_t busy = 0;
@@ -318,7 +329,7 @@ __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
           for (int ks = 0; ks < PF_K; ++ks) read_k(ks);
         }
         s16x4 va[2][C::DT][2];
-        const unsigned char* sV = lds + V_OFF + bp * C::TILE_BYTES + hp * 32 * C::ROW_BYTES;
+        const unsigned char* sV = lds + bp * C::TILE_BYTES + hp * 32 * C::ROW_BYTES;   // V_OFF is inside v_rd
         auto read_v = [&](int ks) {
 #pragma unroll
           for (int dt = 0; dt < C::DT; ++dt) {
@@ -645,13 +656,9 @@ hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
 
 hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, int P, hipStream_t stream) {
   hipError_t e;
-  // 128-token blocks: 1 = eight waves of 32 queries (two per SIMD), 2 = four waves of 64 queries
-  static const int qt128 = [] {
-    const char* s = std::getenv("DBSP_QUERY_TILES");
-    return (s && s[0] == '2') ? 2 : 1;
-  }();
-  if (block == 128 && d == 128) e = (qt128 == 1) ? launch_fwd<128, 128, 1>(p, P, stream) : launch_fwd<128, 128, 2>(p, P, stream);
-  else if (block == 128 && d == 64) e = (qt128 == 1) ? launch_fwd<128, 64, 1>(p, P, stream) : launch_fwd<128, 64, 2>(p, P, stream);
+  // 128-token blocks: eight waves of 32 queries (two per SIMD); 64-token blocks: one wave of 64 queries
+  if (block == 128 && d == 128) e = launch_fwd<128, 128, 1>(p, P, stream);
+  else if (block == 128 && d == 64) e = launch_fwd<128, 64, 1>(p, P, stream);
   else if (block == 64 && d == 128) e = launch_fwd<64, 128, 2>(p, P, stream);
   else if (block == 64 && d == 64) e = launch_fwd<64, 64, 2>(p, P, stream);
   else return hipErrorInvalidValue;
