@@ -37,25 +37,20 @@ def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
     block, d = c["block"], c["d"]
     rng = np.random.default_rng(12345)
     H, nQ, _ = mask.shape
-    order = [(0, int(h), int(I)) for h in range(H) for I in rng.choice(nQ, size=min(nQ, 4), replace=False)]
-    rng.shuffle(order)
     cnt = (mask != 0).sum(2)
-    heads = {}
-    def head_f32(h):
-        if h not in heads:
-            heads.clear()
-            heads[h] = tuple(synth.bf16_bits_to_f32(x[:, h:h + 1]) for x in (qb, kb, vb))
-        return heads[h]
     t_used, blocks, rows = 0.0, 0, 0
-    for (b, h, I) in order:
-        q32, k32, v32 = head_f32(h)
-        t0 = time.perf_counter()
-        oa.masked_attention_rows(q32, k32, v32, mask[h:h + 1], block, [(0, 0, I)])
-        t_used += time.perf_counter() - t0
-        blocks += int(cnt[h, I])
-        rows += 1
-        if t_used >= budget_s:
-            break
+    for h in range(H):                       # an equal share of the budget for every head
+        q32, k32, v32 = (synth.bf16_bits_to_f32(x[:, h:h + 1]) for x in (qb, kb, vb))
+        t_head = 0.0
+        for I in rng.choice(nQ, size=min(nQ, 32), replace=False):
+            t0 = time.perf_counter()
+            oa.masked_attention_rows(q32, k32, v32, mask[h:h + 1], block, [(0, 0, int(I))])
+            t_head += time.perf_counter() - t0
+            blocks += int(cnt[h, I])
+            rows += 1
+            if t_head >= budget_s / H:
+                break
+        t_used += t_head
     tflops = blocks * 4.0 * block * block * d / t_used / 1e12
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": tflops, "unit": "TFLOP/s (active blocks)", "cores": min(threads, os.cpu_count() or threads),
@@ -73,12 +68,15 @@ def main():
     ap.add_argument("--partitions", type=int, default=0, help="0 = one per compute unit")
     ap.add_argument("--reuse-plan", action="store_true", help="static-mask mode: plan once outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time to spend on the CPU baseline sample")
     ap.add_argument("--compare-placements", action="store_true",
                     help="also time the kernel under the naive and the greedy longest-first placement (extra launches)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (3x), so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE by what they read for a copy of known size")
+    ap.add_argument("--locality-groups", type=int, default=8,
+                    help="round-based placement: keep runs of neighbouring query blocks inside one of G groups of partitions "
+                         "(partition p is in group p mod G; 8 = the XCDs of an MI355X, each with its own L2); 0 or 1 = one group")
     ap.add_argument("--item-overhead", type=int, default=0, help="per-item cost, in blocks, the placement adds to an item's weight")
     ap.add_argument("--fit-cost-model", action="store_true",
                     help="also fit time = a*blocks + c*items + t0 on per-partition busy times of extra launches under several "
@@ -110,7 +108,8 @@ def main():
     flops = float(B) * nnz * 4.0 * block * block * d
 
     def one_plan(mode):
-        return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead)
+        return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead,
+                                     locality_groups=args.locality_groups if mode == dbsp.MODE_ROUNDS else 0)
 
     def measured_rho(plan):
         ticks, hw = plan.busy()
@@ -237,7 +236,7 @@ def main():
         "config": {"workload": f"config {cfg}: {c['name']} B={B} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={d} block={block}, "
                                f"nnz={nnz} active blocks (density {nnz / mask.size:.3f})",
                    "step": "plan_sparse_attn + sparse_attn_fwd" if static_plan is None else "sparse_attn_fwd (plan reused)",
-                   "partitions": hst["num_partitions"], "placement": "rounds"},
+                   "partitions": hst["num_partitions"], "placement": "rounds", "locality_groups": max(1, args.locality_groups)},
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "kernel_ms": kern_avg,
         "kernel_ms_min": float(np.min(kern_ms)),

@@ -62,6 +62,13 @@ typedef struct dbsp_plan_opts {
   int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
                              (rho_s is always computed from pure block counts). 0 = the paper's cost model */
   int32_t flags;          /* DBSP_PLAN_HOST_ONLY or 0 */
+  int32_t locality_groups; /* DBSP_MODE_ROUNDS only: G > 1 keeps runs of neighbouring query blocks inside one
+                             group of partitions that share a cache (partition p belongs to group p mod G;
+                             on MI355X workgroup p runs on XCD p mod 8, each XCD has its own L2).  A round is
+                             cut into G contiguous chunks of P/G items; chunks go, heaviest first, to the
+                             group with the least accumulated load that has none yet in this round; inside
+                             the group the k-th heaviest item goes to its k-th least-loaded partition.
+                             G must divide P.  0 or 1 = one group (plain rounds) */
 } dbsp_plan_opts;
 
 /*

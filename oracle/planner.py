@@ -132,7 +132,7 @@ def naive_partition(n_items: int, P: int):
     return [i // run for i in range(n_items)]
 
 
-def rounds_partition(item_heads, weights, blocks_per_head, P: int):
+def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int = 1):
     """Round-based greedy placement (locality-preserving variant of the greedy of Alg. 1).
 
     Heads are taken in descending order of their dense-block count (Alg. 1's sort of
@@ -142,8 +142,17 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int):
     most one item per round and all partitions work on the same head at about the same
     time.  This trades a little balance for data reuse, the trade-off the paper steers with
     its reward factor R_b (Methodology, "Block-level Partitioning", overhead mitigation).
+
+    With groups = G > 1 (G divides P; partition p belongs to group p mod G -- the partitions
+    that share a cache) the round is first cut into G contiguous chunks of P/G items, i.e.
+    runs of neighbouring query blocks.  Chunks are handed to groups by the same greedy one
+    level up: heaviest chunk first (stable), each to the group with the least accumulated
+    load that has not received a chunk in this round (ties: lowest index).  Inside its group
+    a chunk is spread as before: k-th heaviest item to the group's k-th least-loaded partition.
     Returns (assignment per item, the item sequence).
     """
+    if groups < 1 or P % groups != 0:
+        raise ValueError("groups must divide the number of partitions")
     H = len(blocks_per_head)
     head_order = sorted(range(H), key=lambda h: -blocks_per_head[h])
     by_head = [[] for _ in range(H)]
@@ -152,12 +161,20 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int):
     seq = [i for h in head_order for i in by_head[h]]
     assign = [0] * len(weights)
     load = [0] * P
+    per = P // groups
     for r0 in range(0, len(seq), P):
-        idx = sorted(seq[r0:r0 + P], key=lambda i: -weights[i])
-        parts = sorted(range(P), key=lambda g: load[g])
-        for k, i in enumerate(idx):
-            assign[i] = parts[k]
-            load[parts[k]] += weights[i]
+        rnd = seq[r0:r0 + P]
+        chunks = [rnd[j * per:(j + 1) * per] for j in range(groups)]
+        chunk_order = sorted(range(groups), key=lambda j: -sum(weights[i] for i in chunks[j]))
+        free = list(range(groups))
+        for j in chunk_order:
+            gamma = min(free, key=lambda g: (sum(load[p] for p in range(g, P, groups)), g))
+            free.remove(gamma)
+            idx = sorted(chunks[j], key=lambda i: -weights[i])
+            parts = sorted(range(gamma, P, groups), key=lambda p: load[p])
+            for k, i in enumerate(idx):
+                assign[i] = parts[k]
+                load[parts[k]] += weights[i]
     return assign, seq
 
 
@@ -221,7 +238,7 @@ def carry_over_partition(previous, items, nQ: int, P: int):
 
 
 def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0,
-         previous=None, reuse_threshold: float = 1.0):
+         previous=None, reuse_threshold: float = 1.0, locality_groups: int = 1):
     """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly).
 
     With `previous` (a plan of the same geometry and P), the previous placement is kept when the
@@ -259,7 +276,7 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     elif mode == MODE_NAIVE:
         assign = nv_assign
     else:
-        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P)
+        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P, max(1, locality_groups))
 
     # per-partition lists: ascending item id = ascending (head, q_block, kv_begin); for the
     # round-based placement, the order of the rounds

@@ -36,7 +36,7 @@ class DbspError(RuntimeError):
 
 class PlanOpts(C.Structure):
     _fields_ = [("num_partitions", C.c_int32), ("mode", C.c_int32), ("max_item_len", C.c_int32),
-                ("item_overhead", C.c_int32), ("flags", C.c_int32)]
+                ("item_overhead", C.c_int32), ("flags", C.c_int32), ("locality_groups", C.c_int32)]
 
 
 _lib = None
@@ -145,26 +145,27 @@ class Plan:
 
 
 def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
-                     max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False) -> Plan:
+                     max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False,
+                     locality_groups: int = 0) -> Plan:
     """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.ndim != 3:
         raise ValueError("mask must be [H, nQ, nK]")
     H, nQ, nK = mask.shape
-    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0)
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups)
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
     return Plan(out.value, H, nQ, nK, block)
 
 
 def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,
-                           max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False):
+                           max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False, locality_groups: int = 0):
     """Plan the next mask of a sequence, keeping `previous`'s placement while rho_s under it stays
     <= reuse_threshold (see dbsp.h: plan_sparse_attn_reuse).  Returns (Plan, reused, rho_under_previous)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.shape != (previous.H, previous.nQ, previous.nK):
         raise ValueError("mask shape differs from the previous plan's")
-    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0)
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups)
     out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
     _check(load_library().plan_sparse_attn_reuse(previous.handle, mask.ctypes.data_as(C.c_void_p), C.byref(opts),
                                                  float(reuse_threshold), C.byref(out), C.byref(reused), C.byref(rho)))

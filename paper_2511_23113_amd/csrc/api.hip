@@ -213,8 +213,8 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
   if (o.num_partitions < 0 || o.item_overhead < 0 || (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS) ||
-      (o.flags & ~DBSP_PLAN_HOST_ONLY))
-    return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, unknown mode or flag)");
+      (o.flags & ~DBSP_PLAN_HOST_ONLY) || o.locality_groups < 0)
+    return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, groups < 0, unknown mode or flag)");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
   int32_t P = o.num_partitions;
   if (P == 0 && previous) P = previous->host.P;
@@ -233,10 +233,12 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   }
   if (previous && (previous->host.H != H || previous->host.nQ != nQ || previous->host.nK != nK || previous->host.P != P))
     return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan has a different geometry or partition count");
+  if (o.locality_groups > 1 && P % o.locality_groups != 0)
+    return fail(DBSP_EINVAL, std::string(who) + ": locality_groups must divide the number of partitions");
   dbsp_plan* plan = new (std::nothrow) dbsp_plan();
   if (!plan) return fail(DBSP_ENOMEM, std::string(who) + ": out of host memory");
   std::string err;
-  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead,
+  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups,
                                 previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
   if (rc != DBSP_OK) {
     delete plan;

@@ -95,7 +95,7 @@ double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions) {
 
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                          int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                         const dbsp_host_plan* prev, double reuse_threshold,
+                         int32_t locality_groups, const dbsp_host_plan* prev, double reuse_threshold,
                          dbsp_host_plan& hp, std::string& err) {
   try {
     const int64_t R = (int64_t)H * nQ;
@@ -231,17 +231,40 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       for (int32_t h : head_order)
         for (int64_t i = head_begin[h]; i < head_begin[h + 1]; ++i) seq.push_back((int32_t)i);
       assign_rounds.assign(n_items, 0);
-      std::vector<int64_t> load(P, 0);
-      std::vector<int32_t> parts(P), idx;
+      // With G > 1 locality groups (partition p belongs to group p mod G: the partitions behind
+      // one cache) a round is cut into G contiguous chunks of P/G items -- runs of neighbouring
+      // query blocks -- and the same greedy runs one level up: heaviest chunk first, each to the
+      // least-loaded group that has no chunk yet in this round.
+      const int32_t G = locality_groups > 1 ? locality_groups : 1, per = P / G;
+      std::vector<int64_t> load(P, 0), chunk_w(G), group_load(G);
+      std::vector<int32_t> parts(per), idx, chunk_order(G);
+      std::vector<char> taken(G);
       for (int64_t r0 = 0; r0 < n_items; r0 += P) {
         const int64_t r1 = std::min<int64_t>(n_items, r0 + P);
-        idx.assign(seq.begin() + r0, seq.begin() + r1);
-        std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) { return weight(a) > weight(b); });
-        for (int32_t g = 0; g < P; ++g) parts[g] = g;
-        std::stable_sort(parts.begin(), parts.end(), [&](int32_t a, int32_t b) { return load[a] < load[b]; });
-        for (size_t k = 0; k < idx.size(); ++k) {
-          assign_rounds[idx[k]] = parts[k];
-          load[parts[k]] += weight(idx[k]);
+        for (int32_t j = 0; j < G; ++j) {
+          chunk_w[j] = 0;
+          for (int64_t t = r0 + (int64_t)j * per; t < std::min<int64_t>(r1, r0 + (int64_t)(j + 1) * per); ++t) chunk_w[j] += weight(seq[t]);
+          chunk_order[j] = j;
+          taken[j] = 0;
+          group_load[j] = 0;
+        }
+        for (int32_t p = 0; p < P; ++p) group_load[p % G] += load[p];
+        std::stable_sort(chunk_order.begin(), chunk_order.end(), [&](int32_t a, int32_t b) { return chunk_w[a] > chunk_w[b]; });
+        for (int32_t j : chunk_order) {
+          int32_t gamma = -1;
+          for (int32_t g = 0; g < G; ++g)
+            if (!taken[g] && (gamma < 0 || group_load[g] < group_load[gamma])) gamma = g;
+          taken[gamma] = 1;
+          const int64_t c0 = r0 + (int64_t)j * per, c1 = std::min<int64_t>(r1, c0 + per);
+          if (c0 >= c1) continue;
+          idx.assign(seq.begin() + c0, seq.begin() + c1);
+          std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) { return weight(a) > weight(b); });
+          for (int32_t k = 0; k < per; ++k) parts[k] = gamma + k * G;
+          std::stable_sort(parts.begin(), parts.end(), [&](int32_t a, int32_t b) { return load[a] < load[b]; });
+          for (size_t k = 0; k < idx.size(); ++k) {
+            assign_rounds[idx[k]] = parts[k];
+            load[parts[k]] += weight(idx[k]);
+          }
         }
       }
     }

@@ -88,9 +88,10 @@ def test_imbalance_ratio_matches_oracle_and_hand_values():
         assert B.imbalance_ratio(w) == op.imbalance_ratio(w.tolist())
 
 
-def _assert_plan_equal(mask, block, P, mode, L, c0):
-    pl = B.plan_sparse_attn(mask, block, num_partitions=P, mode=mode, max_item_len=L, item_overhead=c0, host_only=True)
-    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0)
+def _assert_plan_equal(mask, block, P, mode, L, c0, G=0):
+    pl = B.plan_sparse_attn(mask, block, num_partitions=P, mode=mode, max_item_len=L, item_overhead=c0, host_only=True,
+                            locality_groups=G)
+    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0, locality_groups=G)
     st = pl.stats()
     assert st["nnz"] == ref["nnz"] and st["n_items"] == len(ref["items"])
     assert st["num_partitions"] == P and st["max_item_len"] == ref["max_item_len"]
@@ -229,3 +230,29 @@ def test_plan_reuse_argument_errors():
     assert lib.plan_sparse_attn_reuse(pl.handle, mp, C.byref(host), 1.1, C.byref(out), None, None) == B.DBSP_OK
     lib.dbsp_plan_destroy(out)
     pl.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 5])
+def test_rounds_with_locality_groups_bit_exact(cfg):
+    mask = synth.mask_for_config(cfg)
+    block = synth.CONFIGS[cfg]["block"]
+    for P, G in ((256, 8), (256, 2), (64, 8), (8, 8), (24, 4)):
+        _assert_plan_equal(mask, block, P, B.MODE_ROUNDS, 0, 0, G)
+    _assert_plan_equal(mask, block, 256, B.MODE_ROUNDS, 16, 2, 8)
+
+
+def test_locality_groups_random_and_errors():
+    rng = np.random.default_rng(77)
+    for seed in range(8):
+        H, nQ, nK = int(rng.integers(1, 5)), int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0.0, 1.0)), seed=seed)
+        for P, G in ((4, 2), (12, 4), (6, 6), (5, 1), (9, 3)):
+            _assert_plan_equal(mask, 64, P, B.MODE_ROUNDS, 0, 0, G)
+            _assert_plan_equal(mask, 64, P, B.MODE_ROUNDS, 2, 1, G)
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    mp = m.ctypes.data_as(C.c_void_p)
+    assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(6, B.MODE_ROUNDS, 0, 0, B.PLAN_HOST_ONLY, 4))[0] == B.DBSP_EINVAL
+    assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(6, B.MODE_ROUNDS, 0, 0, B.PLAN_HOST_ONLY, -1))[0] == B.DBSP_EINVAL
+    rc, pl = _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(6, B.MODE_ROUNDS, 0, 0, B.PLAN_HOST_ONLY, 3))
+    assert rc == B.DBSP_OK
+    B.load_library().dbsp_plan_destroy(pl)

@@ -138,13 +138,14 @@ def _sample_rows(mask, per_head, seed):
 
 @pytest.mark.parametrize("cfg,per_head", [(2, 2), (3, 2), (5, 4), (4, 1)])
 def test_full_size_configs_sampled_rows(cfg, per_head):
-    # the launch configuration the benchmark times: default partitions, round-based placement
+    # the launch configuration the benchmark times: default partitions, round-based placement with
+    # one locality group per XCD
     c = synth.config_shape(cfg)
     block, d = c["block"], c["d"]
     mask = synth.mask_for_config(cfg)
     qb, kb, vb = synth.qkv_for_config(cfg, c["B"], c["H"], c["Nq"], c["Nk"], d)
-    plan, O, L = _run(mask, block, qb, kb, vb, mode=op.MODE_ROUNDS)
-    ref = op.plan(mask, plan.stats()["num_partitions"], mode=op.MODE_ROUNDS)
+    plan, O, L = _run(mask, block, qb, kb, vb, mode=op.MODE_ROUNDS, locality_groups=8)
+    ref = op.plan(mask, plan.stats()["num_partitions"], mode=op.MODE_ROUNDS, locality_groups=8)
     rows = _sample_rows(mask, per_head, seed=cfg)
     # every split row's chunks sit in different partitions: add some split rows and their neighbours
     for r, _, _ in ref["split_rows"][:6]:

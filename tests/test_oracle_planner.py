@@ -295,3 +295,41 @@ def test_reuse_never_exceeds_the_threshold_and_lists_stay_a_partition():
             assert ref["rho_plan"] == ref["rho_reuse"] <= 1.05
         else:
             assert ref["rho_reuse"] > 1.05 and ref["rho_plan"] == ref["rho_balanced"]
+
+
+def test_rounds_with_locality_groups_by_hand():
+    # one head, 8 whole-row items of weights 5,4,1,1, 3,3,2,2 on P = 4 partitions in G = 2 groups
+    # (group 0 = partitions {0, 2}, group 1 = {1, 3}); rounds of 4 items, chunks of 2.
+    # round 0: chunks (5,4)=9 and (1,1)=2: heavier first -> group 0 (both empty, lowest index): 5 -> p0, 4 -> p2;
+    #          then (1,1) -> group 1: 1 -> p1, 1 -> p3.            loads p0..p3 = 5, 1, 4, 1
+    # round 1: chunks (3,3)=6 and (2,2)=4: (3,3) -> least-loaded group = group 1 (2 < 9): p1, p3 (tie, lowest first);
+    #          (2,2) -> group 0: heaviest to least loaded: p2 (4), then p0 (5).  loads = 7, 4, 6, 4
+    w = [5, 4, 1, 1, 3, 3, 2, 2]
+    assign, seq = op.rounds_partition([0] * 8, w, [sum(w)], 4, groups=2)
+    assert seq == list(range(8)) and assign == [0, 2, 1, 3, 1, 3, 2, 0]
+    # one group is the plain round-based placement
+    a1, _ = op.rounds_partition([0] * 8, w, [sum(w)], 4, groups=1)
+    a0, _ = op.rounds_partition([0] * 8, w, [sum(w)], 4)
+    assert a1 == a0
+    with pytest.raises(ValueError):
+        op.rounds_partition([0] * 8, w, [sum(w)], 4, groups=3)
+
+
+def test_locality_groups_keep_neighbouring_rows_together_and_stay_balanced():
+    mask = synth.mask_for_config(5)
+    P, G = 256, 8
+    pl = op.plan(mask, P, mode=op.MODE_ROUNDS, locality_groups=G)
+    assert sorted(pl["part_items"]) == list(range(len(pl["items"])))
+    assert pl["rho_plan"] < 1.10
+    # every round's chunk of P/G consecutive sequence positions sits in one group
+    part_of = {}
+    for g in range(P):
+        for i in pl["part_items"][pl["part_ptr"][g]:pl["part_ptr"][g + 1]]:
+            part_of[i] = g
+    heads = sorted(range(mask.shape[0]), key=lambda h: -pl["blocks_per_head"][h])
+    seq = [i for h in heads for i, it in enumerate(pl["items"]) if it[0] == h]
+    for r0 in range(0, len(seq), P):
+        for j in range(G):
+            chunk = seq[r0 + j * (P // G): r0 + (j + 1) * (P // G)]
+            assert len({part_of[i] % G for i in chunk}) <= 1
+            assert len({part_of[i] for i in chunk}) == len(chunk)      # one item per partition
