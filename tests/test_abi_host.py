@@ -256,3 +256,22 @@ def test_locality_groups_random_and_errors():
     rc, pl = _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(6, B.MODE_ROUNDS, 0, 0, B.PLAN_HOST_ONLY, 3))
     assert rc == B.DBSP_OK
     B.load_library().dbsp_plan_destroy(pl)
+
+
+def test_threaded_compaction_with_empty_and_tiny_rows_bit_exact():
+    # a mask large enough for the multi-threaded row passes, with runs of empty rows and rows of one
+    # or two blocks around the places where the row ranges of the threads meet
+    rng = np.random.default_rng(2024)
+    H, nQ, nK = 8, 512, 520                       # 2.1 MB; nK not a multiple of 8 (scalar tail)
+    mask = (rng.random((H, nQ, nK)) < 0.2).astype(np.uint8)
+    flat = mask.reshape(H * nQ, nK)
+    flat[rng.random(H * nQ) < 0.3] = 0
+    for t in range(1, 8):                         # ranges meet at R * t / n for n = 2..8 threads
+        for n in range(2, 9):
+            r = H * nQ * t // n
+            flat[max(0, r - 3):r] = 0
+            if r - 4 >= 0:
+                flat[r - 4] = 0
+                flat[r - 4, rng.integers(0, nK, 2)] = 1
+    _assert_plan_equal(mask, 128, 256, B.MODE_BALANCED, 0, 0)
+    _assert_plan_equal(mask, 128, 256, B.MODE_ROUNDS, 0, 0, 8)
