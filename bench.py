@@ -23,10 +23,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
 
-# HBM-side bytes per launch of dbsp_fwd_kernel (rounds placement), from rocprofv3 --pmc runs of this
+# HBM-side bytes per launch of dbsp_fwd_kernel (default placement), from rocprofv3 --pmc runs of this
 # command: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy
 # (see profiles/dbsp_fwd_kernel_wan480p_pmc.md).  Keyed by workload config; null when not measured.
-MEASURED_TRAFFIC = {3: 16.6e9}
+MEASURED_TRAFFIC = {3: 12.3e9}
 
 
 def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
@@ -245,7 +245,7 @@ def main():
         "imbalance": {"rho_s_planned": planned, "rho_busy_per_cu": rho_busy, "cus_seen": cus_seen,
                       "placement_timed": "rounds", **({"compare": side} if side else {})},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg),
+                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg) if (args.locality_groups == 8 and args.partitions == 0) else None,
                      "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops},
     }
     if cost is not None:
