@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--locality-groups", type=int, default=8,
                     help="round-based placement: keep runs of neighbouring query blocks inside one of G groups of partitions "
                          "(partition p is in group p mod G; 8 = the XCDs of an MI355X, each with its own L2); 0 or 1 = one group")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="feed the per-compute-unit speeds measured in the last warm-up launch back into the placement "
+                         "(worth about 1 %% once clocks have settled: use a long warm-up)")
     ap.add_argument("--item-overhead", type=int, default=0, help="per-item cost, in blocks, the placement adds to an item's weight")
     ap.add_argument("--fit-cost-model", action="store_true",
                     help="also fit time = a*blocks + c*items + t0 on per-partition busy times of extra launches under several "
@@ -107,9 +110,12 @@ def main():
     nnz = int((mask != 0).sum())
     flops = float(B) * nnz * 4.0 * block * block * d
 
+    part_cost = {"v": None}  # relative time per block of every partition, measured in the last warm-up launch
+
     def one_plan(mode):
         return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead,
-                                     locality_groups=args.locality_groups if mode == dbsp.MODE_ROUNDS else 0)
+                                     locality_groups=args.locality_groups if mode == dbsp.MODE_ROUNDS else 0,
+                                     partition_cost=part_cost["v"] if mode != dbsp.MODE_NAIVE else None)
 
     def measured_rho(plan):
         ticks, hw = plan.busy()
@@ -188,6 +194,8 @@ def main():
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
+    if args.calibrate and static_plan is None and plans:
+        part_cost["v"] = plans[-1].calibrate()          # compute units differ by a few percent, systematically
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i, True)
@@ -243,7 +251,10 @@ def main():
         "plan_ms": float(np.mean(plan_us)) / 1e3 if plan_us else None,
         "plan_pct_of_kernel": (float(np.mean(plan_us)) / 1e3 / kern_avg * 100.0) if plan_us else None,
         "imbalance": {"rho_s_planned": planned, "rho_busy_per_cu": rho_busy, "cus_seen": cus_seen,
-                      "placement_timed": "rounds", **({"compare": side} if side else {})},
+                      "placement_timed": "rounds",
+                      "partition_cost": None if part_cost["v"] is None else {"min": int(part_cost["v"].min()), "max": int(part_cost["v"].max()),
+                                                                          "unit": "1024 = mean time per block"},
+                      **({"compare": side} if side else {})},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg) if (args.locality_groups == 8 and args.partitions == 0) else None,
                      "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops},

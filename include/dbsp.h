@@ -69,6 +69,11 @@ typedef struct dbsp_plan_opts {
                              group with the least accumulated load that has none yet in this round; inside
                              the group the k-th heaviest item goes to its k-th least-loaded partition.
                              G must divide P.  0 or 1 = one group (plain rounds) */
+  const int32_t* partition_cost; /* host, int32 [P] or NULL: relative time partition g needs per block (> 0), e.g.
+                             from dbsp_plan_calibrate.  The greedy placements (balanced, rounds) then compare
+                             accumulated time, sum of weight * cost[g], instead of accumulated weight (list
+                             scheduling on compute units of different speed); equal costs or NULL give the
+                             paper's rule.  Read during the call only.  rho_s stays on pure block counts */
 } dbsp_plan_opts;
 
 /*
@@ -240,6 +245,14 @@ int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_
 int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, double* rho_plan,
                     int64_t* nnz, int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
                     double* plan_usec);
+
+/* dbsp_plan_calibrate: relative time per block of every partition in the LAST sparse_attn_fwd on this plan,
+ * for dbsp_plan_opts.partition_cost of later plans with the same partition count (compute units of one
+ * chip differ by a few percent in speed, systematically).  cost: host, int32 [P], written:
+ * cost[g] = round(1024 * (busy[g] / load[g]) / (sum busy / sum load)) in exact integer arithmetic (round
+ * half up), clamped to [512, 2048]; 1024 for a partition without work or measurement.  Synchronises
+ * `stream` before reading.  Errors: DBSP_EINVAL (null pointer, host-only plan), DBSP_EHIP. */
+int dbsp_plan_calibrate(const dbsp_plan* plan, int32_t* cost, void* stream);
 
 /* dbsp_plan_busy: per-partition busy time of the LAST sparse_attn_fwd on this plan.
  * busy_ticks: host, uint64 [P], ticks of the 100 MHz constant clock summed over the partition's

@@ -108,16 +108,22 @@ def make_items(cnt, nQ: int, max_len: int):
     return items, slot, split_rows
 
 
-def lpt_partition(weights, P: int):
-    """Greedy of Alg. 1 (first loop): returns (assignment per item, load per partition)."""
+def lpt_partition(weights, P: int, cost=None):
+    """Greedy of Alg. 1 (first loop): returns (assignment per item, load per partition).
+
+    cost[g] (positive integers, optional) is the relative time partition g needs per unit of
+    weight; the greedy then compares accumulated time, sum of weight * cost[g], instead of
+    accumulated weight (list scheduling on machines of different speed).  Equal costs give the
+    paper's rule."""
+    cost = [1] * P if cost is None else [int(x) for x in cost]
     order = sorted(range(len(weights)), key=lambda i: -weights[i])   # Python's sort is stable
-    heap = [(0, g) for g in range(P)]                                # (load, index): lowest index wins ties
+    heap = [(0, g) for g in range(P)]                                # (time, index): lowest index wins ties
     heapq.heapify(heap)
     assign = [0] * len(weights)
     for i in order:
-        load, g = heapq.heappop(heap)
+        t, g = heapq.heappop(heap)
         assign[i] = g
-        heapq.heappush(heap, (load + weights[i], g))
+        heapq.heappush(heap, (t + weights[i] * cost[g], g))
     loads = [0] * P
     for i, g in enumerate(assign):
         loads[g] += weights[i]
@@ -132,7 +138,7 @@ def naive_partition(n_items: int, P: int):
     return [i // run for i in range(n_items)]
 
 
-def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int = 1):
+def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int = 1, cost=None):
     """Round-based greedy placement (locality-preserving variant of the greedy of Alg. 1).
 
     Heads are taken in descending order of their dense-block count (Alg. 1's sort of
@@ -149,8 +155,10 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int =
     level up: heaviest chunk first (stable), each to the group with the least accumulated
     load that has not received a chunk in this round (ties: lowest index).  Inside its group
     a chunk is spread as before: k-th heaviest item to the group's k-th least-loaded partition.
+    With cost[g] given (see lpt_partition) "load" is accumulated time, weight * cost[g], everywhere.
     Returns (assignment per item, the item sequence).
     """
+    cost = [1] * P if cost is None else [int(x) for x in cost]
     if groups < 1 or P % groups != 0:
         raise ValueError("groups must divide the number of partitions")
     H = len(blocks_per_head)
@@ -174,7 +182,7 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int =
             parts = sorted(range(gamma, P, groups), key=lambda p: load[p])
             for k, i in enumerate(idx):
                 assign[i] = parts[k]
-                load[parts[k]] += weights[i]
+                load[parts[k]] += weights[i] * cost[parts[k]]
     return assign, seq
 
 
@@ -238,7 +246,7 @@ def carry_over_partition(previous, items, nQ: int, P: int):
 
 
 def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0,
-         previous=None, reuse_threshold: float = 1.0, locality_groups: int = 1):
+         previous=None, reuse_threshold: float = 1.0, locality_groups: int = 1, partition_cost=None):
     """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly).
 
     With `previous` (a plan of the same geometry and P), the previous placement is kept when the
@@ -252,7 +260,7 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     lens = [e - b for (_, _, b, e) in items]
     weights = [ln + item_overhead for ln in lens]
 
-    lpt_assign, _ = lpt_partition(weights, P)
+    lpt_assign, _ = lpt_partition(weights, P, partition_cost)
     nv_assign = naive_partition(len(items), P)
 
     def loads_of(assign):
@@ -276,7 +284,7 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     elif mode == MODE_NAIVE:
         assign = nv_assign
     else:
-        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P, max(1, locality_groups))
+        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P, max(1, locality_groups), partition_cost)
 
     # per-partition lists: ascending item id = ascending (head, q_block, kv_begin); for the
     # round-based placement, the order of the rounds
@@ -299,3 +307,23 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
         rho_naive=rho_naive, rho_balanced=rho_bal, rho_plan=imbalance_ratio([loads_of(assign)]),
         reused=reused, rho_reuse=rho_reuse,
     )
+
+
+def calibrate_cost(busy, load):
+    """Relative time per block of every partition from one launch's busy times, as integers with
+    mean about 1024: cost[g] = round(1024 * (busy[g] / load[g]) / (sum busy / sum load)), in
+    exact integer arithmetic (round half up), clamped to [512, 2048]; 1024 for a partition
+    without work or without a measurement.  Feeding it back to the placement evens out compute
+    units that run at different speeds (the paper fits its latency constants from profiles:
+    Methodology, "Sparsity-aware Strategy Selection")."""
+    pairs = [(int(b), int(l)) for b, l in zip(busy, load)]
+    sb = sum(b for b, l in pairs if b > 0 and l > 0)
+    sl = sum(l for b, l in pairs if b > 0 and l > 0)
+    out = []
+    for b, l in pairs:
+        if b <= 0 or l <= 0 or sb == 0:
+            out.append(1024)
+            continue
+        num, den = b * 1024 * sl, l * sb
+        out.append(min(2048, max(512, (2 * num + den) // (2 * den))))
+    return out

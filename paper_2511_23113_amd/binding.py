@@ -23,7 +23,7 @@ _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 
 EXPORTS = (
     "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
-    "dbsp_plan_busy", "dbsp_plan_destroy", "dbsp_last_error",
+    "dbsp_plan_busy", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
     "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model",
 )
 
@@ -36,7 +36,8 @@ class DbspError(RuntimeError):
 
 class PlanOpts(C.Structure):
     _fields_ = [("num_partitions", C.c_int32), ("mode", C.c_int32), ("max_item_len", C.c_int32),
-                ("item_overhead", C.c_int32), ("flags", C.c_int32), ("locality_groups", C.c_int32)]
+                ("item_overhead", C.c_int32), ("flags", C.c_int32), ("locality_groups", C.c_int32),
+                ("partition_cost", C.c_void_p)]
 
 
 _lib = None
@@ -66,6 +67,8 @@ def load_library(path: str | None = None):
     lib.dbsp_ring_work.restype = C.c_int
     lib.dbsp_fit_cost_model.argtypes = [vp, vp, vp, i32, C.POINTER(f64), C.POINTER(f64), C.POINTER(f64), C.POINTER(f64)]
     lib.dbsp_fit_cost_model.restype = C.c_int
+    lib.dbsp_plan_calibrate.argtypes = [vp, vp, vp]
+    lib.dbsp_plan_calibrate.restype = C.c_int
     lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
     lib.sparse_attn_fwd.restype = C.c_int
     lib.imbalance_ratio.argtypes = [vp, i32, i32, C.POINTER(C.c_double)]
@@ -132,6 +135,13 @@ class Plan:
                                              hw.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
         return ticks, hw
 
+    def calibrate(self, stream=None):
+        """Relative time per block of every partition in the last forward call (int32 [P], mean about 1024):
+        pass it as partition_cost to later plans with the same partition count.  Synchronises."""
+        cost = np.zeros(self.stats()["num_partitions"], dtype=np.int32)
+        _check(load_library().dbsp_plan_calibrate(self.handle, cost.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
+        return cost
+
     def close(self):
         if self._h:
             load_library().dbsp_plan_destroy(self._h)
@@ -146,26 +156,41 @@ class Plan:
 
 def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
                      max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False,
-                     locality_groups: int = 0) -> Plan:
+                     locality_groups: int = 0, partition_cost=None) -> Plan:
     """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.ndim != 3:
         raise ValueError("mask must be [H, nQ, nK]")
     H, nQ, nK = mask.shape
-    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups)
+    cost = np.ascontiguousarray(partition_cost, dtype=np.int32) if partition_cost is not None else None
+    if cost is not None:
+        if num_partitions == 0:
+            num_partitions = int(cost.shape[0])      # one cost per partition: the array fixes their number
+        if cost.ndim != 1 or cost.shape[0] != num_partitions:
+            raise ValueError("partition_cost must hold one value per partition")
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None)
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
     return Plan(out.value, H, nQ, nK, block)
 
 
 def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,
-                           max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False, locality_groups: int = 0):
+                           max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False, locality_groups: int = 0,
+                           partition_cost=None):
     """Plan the next mask of a sequence, keeping `previous`'s placement while rho_s under it stays
     <= reuse_threshold (see dbsp.h: plan_sparse_attn_reuse).  Returns (Plan, reused, rho_under_previous)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.shape != (previous.H, previous.nQ, previous.nK):
         raise ValueError("mask shape differs from the previous plan's")
-    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups)
+    cost = np.ascontiguousarray(partition_cost, dtype=np.int32) if partition_cost is not None else None
+    if cost is not None:
+        if num_partitions == 0:
+            num_partitions = int(cost.shape[0])      # one cost per partition: the array fixes their number
+        if cost.ndim != 1 or cost.shape[0] != num_partitions:
+            raise ValueError("partition_cost must hold one value per partition")
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None)
     out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
     _check(load_library().plan_sparse_attn_reuse(previous.handle, mask.ctypes.data_as(C.c_void_p), C.byref(opts),
                                                  float(reuse_threshold), C.byref(out), C.byref(reused), C.byref(rho)))

@@ -235,10 +235,13 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan has a different geometry or partition count");
   if (o.locality_groups > 1 && P % o.locality_groups != 0)
     return fail(DBSP_EINVAL, std::string(who) + ": locality_groups must divide the number of partitions");
+  if (o.partition_cost)
+    for (int32_t g = 0; g < P; ++g)
+      if (o.partition_cost[g] <= 0) return fail(DBSP_EINVAL, std::string(who) + ": partition_cost must be positive");
   dbsp_plan* plan = new (std::nothrow) dbsp_plan();
   if (!plan) return fail(DBSP_ENOMEM, std::string(who) + ": out of host memory");
   std::string err;
-  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups,
+  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups, o.partition_cost,
                                 previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
   if (rc != DBSP_OK) {
     delete plan;
@@ -391,6 +394,30 @@ int dbsp_plan_busy(const dbsp_plan* plan, uint64_t* busy_ticks, uint32_t* hw_id,
   DBSP_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
   if (busy_ticks) DBSP_HIP(hipMemcpy(busy_ticks, plan->dev.busy, plan->host.P * sizeof(uint64_t), hipMemcpyDeviceToHost));
   if (hw_id) DBSP_HIP(hipMemcpy(hw_id, plan->dev.hw_id, plan->host.P * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  return DBSP_OK;
+}
+
+int dbsp_plan_calibrate(const dbsp_plan* plan, int32_t* cost, void* stream) {
+  if (!plan || !cost) return fail(DBSP_EINVAL, "dbsp_plan_calibrate: null pointer");
+  if (!plan->dev.resident) return fail(DBSP_EINVAL, "dbsp_plan_calibrate: the plan was built host-only");
+  const int32_t P = plan->host.P;
+  std::vector<uint64_t> busy(P);
+  DBSP_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  DBSP_HIP(hipMemcpy(busy.data(), plan->dev.busy, P * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  // cost[g] = round(1024 * (busy[g] / load[g]) / (sum busy / sum load)), exact, round half up
+  unsigned __int128 sb = 0, sl = 0;
+  for (int32_t g = 0; g < P; ++g)
+    if (busy[g] > 0 && plan->host.part_load[g] > 0) {
+      sb += busy[g];
+      sl += (uint64_t)plan->host.part_load[g];
+    }
+  for (int32_t g = 0; g < P; ++g) {
+    const int64_t l = plan->host.part_load[g];
+    if (busy[g] == 0 || l <= 0 || sb == 0) { cost[g] = 1024; continue; }
+    const unsigned __int128 num = (unsigned __int128)busy[g] * 1024 * sl, den = (unsigned __int128)(uint64_t)l * sb;
+    const unsigned __int128 q = (2 * num + den) / (2 * den);
+    cost[g] = q < 512 ? 512 : q > 2048 ? 2048 : (int32_t)q;
+  }
   return DBSP_OK;
 }
 

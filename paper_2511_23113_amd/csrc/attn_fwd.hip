@@ -46,6 +46,7 @@
 //     transposing read hit distinct bank quarters.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <type_traits>
 
@@ -640,12 +641,17 @@ __global__ __launch_bounds__(256) void dbsp_fixup_kernel(const dbsp_fwd_params p
 template <int BLK, int D, int QT_>
 hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
   using C = Cfg<BLK, D, QT_>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbsp_fwd_kernel<BLK, D, QT_>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  // the dynamic-LDS limit is a per-device function attribute: set it once per device
+  static std::atomic<uint32_t> attr_set_mask{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint32_t bit = 1u << (dev & 31);
+  if (!(attr_set_mask.load(std::memory_order_acquire) & bit)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbsp_fwd_kernel<BLK, D, QT_>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set_mask.fetch_or(bit, std::memory_order_release);
   }
   hipLaunchKernelGGL((dbsp_fwd_kernel<BLK, D, QT_>), dim3(P), dim3(C::NT), C::LDS_BYTES, stream, p, p.row_ptr, p.kv_idx,
                      reinterpret_cast<const int4*>(p.items), p.item_slot, p.part_ptr, p.part_items);

@@ -70,8 +70,8 @@ struct dbsp_plan {
 // rho_s under it does not exceed `reuse_threshold`.
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                          int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                         int32_t locality_groups, const dbsp_host_plan* prev, double reuse_threshold,
-                         dbsp_host_plan& out, std::string& err);
+                         int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
+                         double reuse_threshold, dbsp_host_plan& out, std::string& err);
 
 double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions);
 

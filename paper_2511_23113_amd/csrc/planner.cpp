@@ -83,16 +83,18 @@ inline int32_t* compact_row(const uint8_t* row, int32_t n, int32_t* out) {
 // Binary min-heap over partitions keyed by (load, index): the root is the least-loaded
 // partition, lowest index among equals.  Only the root's key ever grows, so one sift-down
 // per placement is enough.
+// With per-partition costs the key is accumulated time, weight * cost, instead of weight.
 struct LoadHeap {
   std::vector<int64_t> load;
   std::vector<int32_t> heap;  // partition ids
-  explicit LoadHeap(int32_t P) : load(P, 0), heap(P) {
+  const int32_t* cost;        // may be null (unit cost)
+  LoadHeap(int32_t P, const int32_t* cost_) : load(P, 0), heap(P), cost(cost_) {
     for (int32_t g = 0; g < P; ++g) heap[g] = g;  // all loads equal: ascending ids form a valid heap
   }
   bool less(int32_t a, int32_t b) const { return load[a] < load[b] || (load[a] == load[b] && a < b); }
   int32_t place(int64_t w) {
     const int32_t g = heap[0];
-    load[g] += w;
+    load[g] += cost ? w * cost[g] : w;
     const size_t n = heap.size();
     size_t i = 0;
     for (;;) {
@@ -126,8 +128,8 @@ double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions) {
 
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                          int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                         int32_t locality_groups, const dbsp_host_plan* prev, double reuse_threshold,
-                         dbsp_host_plan& hp, std::string& err) {
+                         int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
+                         double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
   try {
     const int64_t R = (int64_t)H * nQ;
     hp.H = H; hp.nQ = nQ; hp.nK = nK; hp.block = block;
@@ -277,7 +279,7 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       for (int64_t w = 0; w <= wmax; ++w) bucket_start[w + 1] += bucket_start[w];
       std::vector<int32_t> order(n_items);
       for (int64_t i = 0; i < n_items; ++i) order[bucket_start[wmax - weight(i)]++] = (int32_t)i;
-      LoadHeap heap(P);
+      LoadHeap heap(P, partition_cost);
       for (int64_t t = 0; t < n_items; ++t) {
         const int32_t i = order[t];
         assign_lpt[i] = heap.place(weight(i));
@@ -334,7 +336,7 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
           std::stable_sort(parts.begin(), parts.end(), [&](int32_t a, int32_t b) { return load[a] < load[b]; });
           for (size_t k = 0; k < idx.size(); ++k) {
             assign_rounds[idx[k]] = parts[k];
-            load[parts[k]] += weight(idx[k]);
+            load[parts[k]] += partition_cost ? weight(idx[k]) * partition_cost[parts[k]] : weight(idx[k]);
           }
         }
       }

@@ -88,10 +88,10 @@ def test_imbalance_ratio_matches_oracle_and_hand_values():
         assert B.imbalance_ratio(w) == op.imbalance_ratio(w.tolist())
 
 
-def _assert_plan_equal(mask, block, P, mode, L, c0, G=0):
+def _assert_plan_equal(mask, block, P, mode, L, c0, G=0, cost=None):
     pl = B.plan_sparse_attn(mask, block, num_partitions=P, mode=mode, max_item_len=L, item_overhead=c0, host_only=True,
-                            locality_groups=G)
-    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0, locality_groups=G)
+                            locality_groups=G, partition_cost=cost)
+    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0, locality_groups=G, partition_cost=cost)
     st = pl.stats()
     assert st["nnz"] == ref["nnz"] and st["n_items"] == len(ref["items"])
     assert st["num_partitions"] == P and st["max_item_len"] == ref["max_item_len"]
@@ -275,3 +275,35 @@ def test_threaded_compaction_with_empty_and_tiny_rows_bit_exact():
                 flat[r - 4, rng.integers(0, nK, 2)] = 1
     _assert_plan_equal(mask, 128, 256, B.MODE_BALANCED, 0, 0)
     _assert_plan_equal(mask, 128, 256, B.MODE_ROUNDS, 0, 0, 8)
+
+
+def test_partition_cost_bit_exact_and_errors():
+    rng = np.random.default_rng(31)
+    for cfg, P in ((5, 256), (1, 8), (3, 256)):
+        mask = synth.mask_for_config(cfg)
+        block = synth.CONFIGS[cfg]["block"]
+        cost = rng.integers(960, 1090, P).tolist()
+        _assert_plan_equal(mask, block, P, B.MODE_BALANCED, 0, 0, 0, cost)
+        _assert_plan_equal(mask, block, P, B.MODE_ROUNDS, 0, 0, 8, cost)
+        _assert_plan_equal(mask, block, P, B.MODE_ROUNDS, 0, 1, 0, cost)
+        _assert_plan_equal(mask, block, P, B.MODE_NAIVE, 0, 0, 0, cost)          # ignored by the naive placement
+        _assert_plan_equal(mask, block, P, B.MODE_BALANCED, 0, 0, 0, [3] * P)    # equal costs: the paper's rule
+    for seed in range(6):
+        H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0, 1)), seed=seed)
+        for P, G in ((4, 2), (6, 3), (5, 1)):
+            cost = rng.integers(1, 50, P).tolist()
+            _assert_plan_equal(mask, 64, P, B.MODE_BALANCED, 2, 1, 0, cost)
+            _assert_plan_equal(mask, 64, P, B.MODE_ROUNDS, 0, 0, G, cost)
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    with pytest.raises(B.DbspError):
+        B.plan_sparse_attn(m, 64, num_partitions=3, host_only=True, partition_cost=[1, 0, 2])
+    with pytest.raises(ValueError):
+        B.plan_sparse_attn(m, 64, num_partitions=3, host_only=True, partition_cost=[1, 2])
+    pl = B.plan_sparse_attn(m, 64, host_only=True, partition_cost=[5, 5, 5, 5])      # the array fixes P
+    assert pl.stats()["num_partitions"] == 4
+    lib = B.load_library()
+    out = np.zeros(4, np.int32)
+    assert lib.dbsp_plan_calibrate(pl.handle, out.ctypes.data_as(C.c_void_p), None) == B.DBSP_EINVAL   # host-only plan
+    assert lib.dbsp_plan_calibrate(None, out.ctypes.data_as(C.c_void_p), None) == B.DBSP_EINVAL
+    pl.close()

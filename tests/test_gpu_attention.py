@@ -281,3 +281,42 @@ def test_cost_model_fitted_on_busy_times_predicts_another_plan():
     pb, pi, pt = sample(dbsp.MODE_BALANCED, 0)
     pred = a * pb + ci * pi + t0
     assert abs(pred.max() - pt.max()) <= 0.15 * pt.max()
+
+
+def test_calibrated_placement_matches_the_oracle_and_evens_out_busy_time():
+    # feed the per-compute-unit speeds of one launch back into the placement: results stay within
+    # tolerance (the placement only changes who computes what) and the busy-time spread does not grow
+    import torch
+    import paper_2511_23113_amd as dbsp
+    from paper_2511_23113_amd import binding as B
+    c = synth.config_shape(5)
+    block, d = c["block"], c["d"]
+    mask = synth.mask_for_config(5)
+    qb, kb, vb = synth.qkv_for_config(5, c["B"], c["H"], c["Nq"], c["Nk"], d)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    first = dbsp.plan_sparse_attn(mask, block, mode=dbsp.MODE_ROUNDS, locality_groups=8)
+    for _ in range(3):
+        dbsp.sparse_attn_fwd(first, q, k, v)
+    cost = first.calibrate()
+    t0, _ = first.busy()
+    load0 = first.array(B.PART_LOAD)
+    assert cost.shape == (first.stats()["num_partitions"],) and cost.min() >= 512 and cost.max() <= 2048
+    assert cost.tolist() == op.calibrate_cost(t0.tolist(), load0.tolist())          # same integers as the oracle
+    assert abs(float(cost.mean()) - 1024) < 40
+    tuned = dbsp.plan_sparse_attn(mask, block, mode=dbsp.MODE_ROUNDS, locality_groups=8, partition_cost=cost)
+    ref = op.plan(mask, tuned.stats()["num_partitions"], mode=op.MODE_ROUNDS, locality_groups=8, partition_cost=cost.tolist())
+    assert tuned.array(B.PART_ITEMS).tolist() == ref["part_items"]
+    for _ in range(2):
+        o, lse = dbsp.sparse_attn_fwd(tuned, q, k, v)
+    t1, _ = tuned.busy()
+    spread0, spread1 = float(t0.max() / t0.mean()), float(t1.max() / t1.mean())
+    assert spread1 <= spread0 + 0.01
+    rows = [(0, h, I) for h, I in ((0, 0), (3, 17), (9, 127), (5, 64))]
+    q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    Or, Lr = oa.masked_attention_rows(q32, k32, v32, mask, block, rows)
+    O = _host_f32(o).reshape(c["B"], c["H"], c["nQ"], block, d)
+    L = lse.cpu().numpy().reshape(c["B"], c["H"], c["nQ"], block)
+    for t, (b, h, I) in enumerate(rows):
+        assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL and np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL
+    first.close()
+    tuned.close()

@@ -333,3 +333,41 @@ def test_locality_groups_keep_neighbouring_rows_together_and_stay_balanced():
             chunk = seq[r0 + j * (P // G): r0 + (j + 1) * (P // G)]
             assert len({part_of[i] % G for i in chunk}) <= 1
             assert len({part_of[i] for i in chunk}) == len(chunk)      # one item per partition
+
+
+def test_cost_weighted_greedy_by_hand():
+    # weights 6,5,4,3 on two partitions, the second twice as slow (cost 1 and 2): accumulated TIME decides.
+    # 6 -> p0 (t = 6, 0).  5 -> p1 (t = 6, 10).  4 -> p0 (t = 10, 10).  3 -> tie at 10 -> p0 (lowest index): t = 13, 10
+    assign, loads = op.lpt_partition([6, 5, 4, 3], 2, cost=[1, 2])
+    assert assign == [0, 1, 0, 0] and loads == [13, 5]
+    # equal costs of any size reproduce the paper's rule
+    rng = np.random.default_rng(4)
+    for _ in range(50):
+        w = rng.integers(0, 40, int(rng.integers(0, 30))).tolist()
+        g = int(rng.integers(1, 7))
+        assert op.lpt_partition(w, g, cost=[9] * g) == op.lpt_partition(w, g)
+        heads = [0] * len(w)
+        assert op.rounds_partition(heads, w, [sum(w)], g, cost=[9] * g) == op.rounds_partition(heads, w, [sum(w)], g)
+    # rounds: weights 4,3 then 2,2 on two partitions with costs 1 and 3.
+    # round 0: 4 -> p0, 3 -> p1 (t = 4, 9).  round 1: 2 -> least time p0, 2 -> p1 (t = 6, 15)
+    assign, _ = op.rounds_partition([0] * 4, [4, 3, 2, 2], [11], 2, cost=[1, 3])
+    assert assign == [0, 1, 0, 1]
+
+
+def test_calibration_by_hand_and_its_effect():
+    # busy 100,110,0,90 over loads 10,10,5,10: mean rate of the measured ones = 300 / 30 = 10 per block
+    # -> 1024 * (10, 11, -, 9) / 10 = 1024, 1126.4 -> 1126, unmeasured -> 1024, 921.6 -> 922
+    assert op.calibrate_cost([100, 110, 0, 90], [10, 10, 5, 10]) == [1024, 1126, 1024, 922]
+    assert op.calibrate_cost([0, 0], [3, 4]) == [1024, 1024]
+    assert op.calibrate_cost([1000, 1], [1, 1000]) == [2048, 512]            # clamped
+    # a partition that is 5 % slow gets about 5 % fewer blocks, and the predicted finish times even out
+    mask = synth.mask_for_config(5)
+    cost = [1075 if g % 8 == 7 else 1024 for g in range(256)]
+    flat = op.plan(mask, 256, mode=op.MODE_BALANCED)
+    tuned = op.plan(mask, 256, mode=op.MODE_BALANCED, partition_cost=cost)
+    t_flat = [l * c for l, c in zip(flat["part_load"], cost)]
+    t_tuned = [l * c for l, c in zip(tuned["part_load"], cost)]
+    assert max(t_tuned) / (sum(t_tuned) / 256) < 1.02 < max(t_flat) / (sum(t_flat) / 256)
+    slow = [tuned["part_load"][g] for g in range(256) if g % 8 == 7]
+    fast = [tuned["part_load"][g] for g in range(256) if g % 8 != 7]
+    assert 0.93 < (sum(slow) / len(slow)) / (sum(fast) / len(fast)) < 0.97
