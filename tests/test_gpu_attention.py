@@ -37,11 +37,16 @@ def _run(mask, block, qb, kb, vb, scale=0.0, want_lse=True, **plan_kw):
     return plan, _host_f32(o), (lse.cpu().numpy() if lse is not None else None)
 
 
-def _check_all_rows(mask, block, qb, kb, vb, O, L, scale=None):
+def _check_all_rows(mask, block, qb, kb, vb, O, L, scale=None, relative_above_one=False):
     q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
     Or, Lr = oa.masked_attention(q32, k32, v32, mask, block, scale=scale)
     assert np.isfinite(O).all()
-    assert np.abs(O - Or).max() <= O_TOL
+    if relative_above_one:
+        # outputs of magnitude 2..4 carry a bf16 rounding error of up to 2^-7 by themselves: the
+        # absolute bound is applied to |O| <= 1 and scaled with |O| beyond
+        assert (np.abs(O - Or) <= O_TOL * np.maximum(1.0, np.abs(Or))).all()
+    else:
+        assert np.abs(O - Or).max() <= O_TOL
     if L is not None:
         empty = np.isneginf(Lr)
         assert np.array_equal(np.isneginf(L), empty)
@@ -320,3 +325,26 @@ def test_calibrated_placement_matches_the_oracle_and_evens_out_busy_time():
         assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL and np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL
     first.close()
     tuned.close()
+
+
+@pytest.mark.parametrize("block,d", [(128, 128), (64, 64)])
+def test_scores_that_keep_growing_take_the_rescale_path(block, d):
+    # keys grow along the sequence and a few are outliers, so the running max rises by more than
+    # the rescale threshold again and again (the speculative softmax must redo those units), and
+    # one query row has near-zero scores only (it never leaves the speculative path)
+    B_, H, nQ, nK = 1, 2, 2, 6
+    mask = np.ones((H, nQ, nK), dtype=np.uint8)
+    mask[1, 0, ::2] = 0
+    rng = np.random.default_rng(99)
+    q = rng.standard_normal((B_, H, nQ * block, d)).astype(np.float32)
+    k = rng.standard_normal((B_, H, nK * block, d)).astype(np.float32)
+    v = rng.standard_normal((B_, H, nK * block, d)).astype(np.float32)
+    k *= np.linspace(0.2, 6.0, nK * block, dtype=np.float32)[None, None, :, None]      # growth along the keys
+    k[:, :, rng.integers(0, nK * block, 12)] *= 4.0                                     # outliers
+    q[:, :, 5] = 1e-3 * q[:, :, 5]                                                      # a flat row
+    qb, kb, vb = (synth.f32_to_bf16_bits(x) for x in (q, k, v))
+    for kw in (dict(num_partitions=4), dict(num_partitions=5, max_item_len=2)):
+        plan, O, L = _run(mask, block, qb, kb, vb, **kw)
+        # scores reach a few hundred here: O stays a convex combination of V rows, LSE is large
+        _check_all_rows(mask, block, qb, kb, vb, O, L, relative_above_one=True)
+        plan.close()
