@@ -12,9 +12,11 @@
 //   * waves form a (query group) x (key half) grid: wave (a, c) owns QT tiles of 32 query columns
 //     and, of every KV block, the keys [c*KW, (c+1)*KW).  Each wave keeps its own running softmax
 //     statistics over its key half; the two key halves are combined once per item.
-//     128-token blocks run QT = 1: eight waves, two per SIMD, 256 registers each, everything in
-//     the arch-VGPR file (the MFMAs read and write it directly, the softmax reads S in place).
-//     64-token blocks run QT = 2 in a single wave (accumulators in accumulation registers).
+//     Every shape runs QT = 1 (eight waves for 128-token blocks, two for 64-token blocks) at two or
+//     three waves per SIMD with everything in the arch-VGPR file: the MFMAs read and write it
+//     directly and the softmax reads S in place.  (QT = 2 -- four waves of 64 queries with the
+//     accumulators in accumulation registers, one wave per SIMD -- is kept as a template option;
+//     it halves the LDS operand reads per MFMA but measured 4-5 % slower.)
 //   * Products are formed transposed, S^T = K Q^T and O^T = V^T P^T, with
 //     v_mfma_f32_32x32x16_bf16: lane r holds query r, so m and l are per-lane scalars.
 //   * S^T's accumulator registers 8h..8h+7 of a 32-key tile hold, in lane group g, the keys
@@ -149,7 +151,8 @@ struct Cfg {
 };
 
 template <int BLK, int D, int QT_>
-__global__ __launch_bounds__(BLK * BLK / (32 * QT_)) void dbsp_fwd_kernel(
+__global__ __launch_bounds__(BLK * BLK / (32 * QT_)) __attribute__((amdgpu_waves_per_eu(QT_ == 1 ? 2 : 1)))
+void dbsp_fwd_kernel(
     const dbsp_fwd_params p, const int32_t* __restrict__ g_row_ptr, const int32_t* __restrict__ g_kv_idx,
     const int4* __restrict__ g_items, const int32_t* __restrict__ g_item_slot,
     const int32_t* __restrict__ g_part_ptr, const int32_t* __restrict__ g_part_items) {
@@ -662,11 +665,11 @@ hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
 
 hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, int P, hipStream_t stream) {
   hipError_t e;
-  // 128-token blocks: eight waves of 32 queries (two per SIMD); 64-token blocks: one wave of 64 queries
+  // waves of 32 queries everywhere: eight per workgroup for 128-token blocks, two for 64-token blocks
   if (block == 128 && d == 128) e = launch_fwd<128, 128, 1>(p, P, stream);
   else if (block == 128 && d == 64) e = launch_fwd<128, 64, 1>(p, P, stream);
-  else if (block == 64 && d == 128) e = launch_fwd<64, 128, 2>(p, P, stream);
-  else if (block == 64 && d == 64) e = launch_fwd<64, 64, 2>(p, P, stream);
+  else if (block == 64 && d == 128) e = launch_fwd<64, 128, 1>(p, P, stream);
+  else if (block == 64 && d == 64) e = launch_fwd<64, 64, 1>(p, P, stream);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   const int fix = p.B * (p.n_split + p.n_empty);
