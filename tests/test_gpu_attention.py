@@ -166,8 +166,12 @@ def test_full_size_configs_sampled_rows(cfg, per_head):
     for t, (b, h, I) in enumerate(rows):
         assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL, (cfg, h, I)
         assert np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL, (cfg, h, I)
-    # properties that hold at any size: finite everywhere, LSE bounded by ln(active keys) + max score bound
+    # properties that hold at any size: finite everywhere; every output row is a convex combination
+    # of V rows of its head, so no component leaves the range V spans in that head
     assert np.isfinite(O).all() and np.isfinite(L).all()
+    vmax = v32.max(axis=2)[:, :, None, None, :] + O_TOL
+    vmin = v32.min(axis=2)[:, :, None, None, :] - O_TOL
+    assert (O <= vmax).all() and (O >= vmin).all()
     st = plan.stats()
     assert st["rho_balanced"] == ref["rho_balanced"] and st["rho_plan"] == ref["rho_plan"] and st["nnz"] == ref["nnz"]
     busy, hw = plan.busy()
