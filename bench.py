@@ -59,6 +59,68 @@ def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
                       f"{t_used:.1f} s of float64 numpy; throughput extrapolated by active-block count"}
 
 
+def extras(dbsp, synth, torch, np, cfg, c, mask, q, k, v, o, lse):
+    """Side measurements (not part of the timed region)."""
+    res = {}
+
+    def timed(plan, qq, kk, vv, oo, ll, reps=3):
+        for _ in range(2):
+            dbsp.sparse_attn_fwd(plan, qq, kk, vv, o=oo, lse=ll)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            dbsp.sparse_attn_fwd(plan, qq, kk, vv, o=oo, lse=ll)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # (1) low-density heads of this config on their own: little KV reuse, so the memory rate is what counts
+    block, d = c["block"], c["d"]
+    dens = (mask != 0).mean(axis=(1, 2))
+    low = np.where(dens < 0.12)[0]
+    if len(low):
+        m2 = mask.copy()
+        m2[[h for h in range(mask.shape[0]) if h not in set(low.tolist())]] = 0
+        plan = dbsp.plan_sparse_attn(m2, block, mode=dbsp.MODE_ROUNDS, locality_groups=8)
+        ms = timed(plan, q, k, v, o, lse)
+        pairs = int((m2 != 0).sum())
+        rows = int(((m2 != 0).sum(2) > 0).sum())
+        alg_bytes = pairs * 4.0 * block * d + rows * (4.0 * block * d + 4.0 * block)       # K+V per pair; Q, O, LSE per row
+        res["low_density_heads"] = {"heads": low.tolist(), "density": [round(float(x), 4) for x in dens[low]], "active_blocks": pairs,
+                                    "kernel_ms": ms, "algorithmic_GB_per_s": alg_bytes / (ms * 1e-3) / 1e9,
+                                    "tflops": pairs * 4.0 * block * block * d / (ms * 1e-3) / 1e12}
+        plan.close()
+
+    # (2) kernel time against the number of active blocks: the cost of a mask is its dense-block count
+    # (paper: Background, "Block-wise Sparse Attention"), so this should be a straight line.  The masks are
+    # config 5's first mask restricted to its first 1..H heads, then the first masks of its sequence.
+    c5 = synth.config_shape(5)
+    qb, kb, vb = synth.qkv_for_config(5, c5["B"], c5["H"], c5["Nq"], c5["Nk"], c5["d"])
+    dev = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    q5, k5, v5 = dev(qb), dev(kb), dev(vb)
+    o5 = torch.empty_like(q5)
+    l5 = torch.empty((c5["B"], c5["H"], c5["Nq"]), dtype=torch.float32, device="cuda")
+    seq = list(synth.mask_sequence_cfg5(8))
+    masks = []
+    for nh in range(1, c5["H"] + 1):
+        m = seq[0].copy()
+        m[nh:] = 0
+        masks.append(m)
+    masks += seq[1:]
+    xs, ys = [], []
+    for m in masks:
+        plan = dbsp.plan_sparse_attn(m, c5["block"], mode=dbsp.MODE_ROUNDS, locality_groups=8)
+        ys.append(timed(plan, q5, k5, v5, o5, l5))
+        xs.append(int((m != 0).sum()))
+        plan.close()
+    xs, ys = np.array(xs, dtype=np.float64), np.array(ys)
+    slope, icpt = np.polyfit(xs, ys, 1)
+    r2 = 1.0 - ((ys - (slope * xs + icpt)) ** 2).sum() / ((ys - ys.mean()) ** 2).sum()
+    res["config5_time_vs_blocks"] = {"masks": len(xs), "blocks": [int(x) for x in xs], "kernel_ms": [round(float(y), 4) for y in ys],
+                                     "us_per_1000_blocks": float(slope * 1e6), "intercept_ms": float(icpt), "r_squared": float(r2)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +139,10 @@ def main():
     ap.add_argument("--locality-groups", type=int, default=8,
                     help="round-based placement: keep runs of neighbouring query blocks inside one of G groups of partitions "
                          "(partition p is in group p mod G; 8 = the XCDs of an MI355X, each with its own L2); 0 or 1 = one group")
+    ap.add_argument("--no-mfma-probe", action="store_true", help="skip the few-millisecond measurement of the chip's sustained MFMA rate")
+    ap.add_argument("--extras", action="store_true",
+                    help="also measure (extra launches, outside the timed region) kernel time against active-block count over the 50 "
+                         "masks of config 5, and the memory rate of the low-density heads of this config run on their own")
     ap.add_argument("--calibrate", action="store_true",
                     help="feed the per-compute-unit speeds measured in the last warm-up launch back into the placement "
                          "(worth about 1 %% once clocks have settled: use a long warm-up)")
@@ -111,6 +177,11 @@ def main():
     flops = float(B) * nnz * 4.0 * block * block * d
 
     part_cost = {"v": None}  # relative time per block of every partition, measured in the last warm-up launch
+
+    sustained = None
+    if not args.no_mfma_probe:
+        tf, ghz = dbsp.mfma_probe()                # back-to-back MFMAs on every compute unit, a few ms
+        sustained = {"mfma_tflops": tf, "clock_ghz": ghz}
 
     def one_plan(mode):
         return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead,
@@ -248,6 +319,8 @@ def main():
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "kernel_ms": kern_avg,
         "kernel_ms_min": float(np.min(kern_ms)),
+        "kernel_ms_median": float(np.median(kern_ms)),
+        "kernel_ms_p95": float(np.percentile(kern_ms, 95)),
         "plan_ms": float(np.mean(plan_us)) / 1e3 if plan_us else None,
         "plan_pct_of_kernel": (float(np.mean(plan_us)) / 1e3 / kern_avg * 100.0) if plan_us else None,
         "imbalance": {"rho_s_planned": planned, "rho_busy_per_cu": rho_busy, "cus_seen": cus_seen,
@@ -257,10 +330,14 @@ def main():
                       **({"compare": side} if side else {})},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg) if (args.locality_groups == 8 and args.partitions == 0) else None,
-                     "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops},
+                     "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops,
+                     **({"sustained_mfma_only": {**sustained, "frac_of_sustained": kern_tflops / sustained["mfma_tflops"]}}
+                        if sustained else {})},
     }
     if cost is not None:
         out["cost_model"] = cost
+    if args.extras:
+        out["extras"] = extras(dbsp, synth, torch, np, cfg, c, mask, q, k, v, o, lse)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=args.cpu_budget)
     print(json.dumps(out))

@@ -148,6 +148,16 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
 int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, double* rho_out);
 
 /*
+ * dbsp_mfma_probe -- the chip's sustained dense bf16 MFMA rate, measured on the spot (diagnostic: the
+ * roofline's published peak assumes 2.4 GHz, the sustained rate shows what clock the chip holds).
+ * Runs a kernel of back-to-back v_mfma_f32_32x32x16_bf16 (eight waves per compute unit) for a few
+ * milliseconds on `stream` and synchronises.  tflops (required): achieved TFLOP/s; clock_ghz (may be
+ * NULL): shader clock during the run.  Allocates and frees a small device buffer.
+ * Errors: DBSP_EINVAL, DBSP_EHIP.
+ */
+int dbsp_mfma_probe(double* tflops, double* clock_ghz, void* stream);
+
+/*
  * dbsp_fit_cost_model -- least-squares fit of  time = a * blocks + c * items + t0  over n
  * per-partition samples (paper: Methodology, "Sparsity-aware Strategy Selection": compute time
  * proportional to the dense-block count plus a constant, constants fitted from profiles; the

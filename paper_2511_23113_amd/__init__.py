@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     fit_cost_model,
     imbalance_ratio,
     load_library,
+    mfma_probe,
     partition_blocks,
     partition_heads,
     plan_sparse_attn,

@@ -24,7 +24,7 @@ _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 EXPORTS = (
     "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
     "dbsp_plan_busy", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
-    "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model",
+    "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model", "dbsp_mfma_probe",
 )
 
 
@@ -67,6 +67,8 @@ def load_library(path: str | None = None):
     lib.dbsp_ring_work.restype = C.c_int
     lib.dbsp_fit_cost_model.argtypes = [vp, vp, vp, i32, C.POINTER(f64), C.POINTER(f64), C.POINTER(f64), C.POINTER(f64)]
     lib.dbsp_fit_cost_model.restype = C.c_int
+    lib.dbsp_mfma_probe.argtypes = [C.POINTER(f64), C.POINTER(f64), vp]
+    lib.dbsp_mfma_probe.restype = C.c_int
     lib.dbsp_plan_calibrate.argtypes = [vp, vp, vp]
     lib.dbsp_plan_calibrate.restype = C.c_int
     lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
@@ -306,3 +308,10 @@ def fit_cost_model(blocks, items, time):
     a, c, t0, rms = C.c_double(), C.c_double(), C.c_double(), C.c_double()
     _check(load_library().dbsp_fit_cost_model(_ptr(b), _ptr(i), _ptr(t), b.shape[0], C.byref(a), C.byref(c), C.byref(t0), C.byref(rms)))
     return a.value, c.value, t0.value, rms.value
+
+
+def mfma_probe(stream=None):
+    """(sustained dense bf16 MFMA TFLOP/s, shader clock in GHz) measured on the current device (see dbsp.h: dbsp_mfma_probe)."""
+    t, g = C.c_double(), C.c_double()
+    _check(load_library().dbsp_mfma_probe(C.byref(t), C.byref(g), _stream_ptr(stream)))
+    return t.value, g.value

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdbsp.so")
 
-SOURCES = ["planner.cpp", "dual_balance.cpp", "cost_model.cpp", "api.hip", "attn_fwd.hip"]
+SOURCES = ["planner.cpp", "dual_balance.cpp", "cost_model.cpp", "api.hip", "attn_fwd.hip", "mfma_probe.hip"]
 
 # Per-file extra flags.  The attention kernels never rely on NaN propagation; without NaN
 # handling the max chains of the softmax compile to v_max3_f32.  (Host-side argument checks in

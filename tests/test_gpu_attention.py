@@ -352,3 +352,10 @@ def test_scores_that_keep_growing_take_the_rescale_path(block, d):
         # scores reach a few hundred here: O stays a convex combination of V rows, LSE is large
         _check_all_rows(mask, block, qb, kb, vb, O, L, relative_above_one=True)
         plan.close()
+
+
+def test_mfma_probe_reports_a_plausible_sustained_rate():
+    import paper_2511_23113_amd as dbsp
+    tflops, ghz = dbsp.mfma_probe()
+    assert 1000.0 < tflops < 2600.0           # below the 2.5 PFLOP/s nominal peak, far above anything but MFMA
+    assert 1.0 < ghz < 2.6
