@@ -42,22 +42,26 @@ int fail_hip(hipError_t e, const char* what) {
 // ---- process-wide resources: upload stream, device and pinned-host buffer pools -------------
 // Plans are created and destroyed per attention call when masks are dynamic, so their buffers are
 // recycled instead of going through hipMalloc / hipFree (which synchronises the device) each time.
+// Entries remember the device that was current when they were allocated and only go back to it.
 struct BufferPool {
-  struct Entry { void* ptr; size_t bytes; };
+  struct Entry { void* ptr; size_t bytes; int device; };
   std::vector<Entry> free_list;
   static constexpr size_t kMaxCached = 8;
 };
 
+constexpr int kMaxDevices = 64;
 std::mutex g_mu;
-hipStream_t g_upload_stream = nullptr;
+hipStream_t g_upload_stream[kMaxDevices] = {};
 BufferPool g_dev_pool, g_pin_pool;
 
-hipError_t pool_get(BufferPool& pool, bool pinned, size_t bytes, void** out, size_t* cap) {
+hipError_t pool_get(BufferPool& pool, bool pinned, int device, size_t bytes, void** out, size_t* cap) {
   {
     std::lock_guard<std::mutex> lk(g_mu);
     int best = -1;
     for (size_t i = 0; i < pool.free_list.size(); ++i)
-      if (pool.free_list[i].bytes >= bytes && (best < 0 || pool.free_list[i].bytes < pool.free_list[best].bytes)) best = (int)i;
+      if (pool.free_list[i].device == device && pool.free_list[i].bytes >= bytes &&
+          (best < 0 || pool.free_list[i].bytes < pool.free_list[best].bytes))
+        best = (int)i;
     if (best >= 0) {
       *out = pool.free_list[best].ptr;
       *cap = pool.free_list[best].bytes;
@@ -71,12 +75,12 @@ hipError_t pool_get(BufferPool& pool, bool pinned, size_t bytes, void** out, siz
   return e;
 }
 
-void pool_put(BufferPool& pool, bool pinned, void* ptr, size_t bytes) {
+void pool_put(BufferPool& pool, bool pinned, int device, void* ptr, size_t bytes) {
   if (!ptr) return;
   void* victim = nullptr;
   {
     std::lock_guard<std::mutex> lk(g_mu);
-    pool.free_list.push_back({ptr, bytes});
+    pool.free_list.push_back({ptr, bytes, device});
     if (pool.free_list.size() > BufferPool::kMaxCached) {
       size_t smallest = 0;
       for (size_t i = 1; i < pool.free_list.size(); ++i)
@@ -88,13 +92,15 @@ void pool_put(BufferPool& pool, bool pinned, void* ptr, size_t bytes) {
   if (victim) (void)(pinned ? hipHostFree(victim) : hipFree(victim));
 }
 
-hipError_t upload_stream(hipStream_t* out) {
+// One upload stream per device (created on first use, with that device current).
+hipError_t upload_stream(int device, hipStream_t* out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
   std::lock_guard<std::mutex> lk(g_mu);
-  if (!g_upload_stream) {
-    hipError_t e = hipStreamCreateWithFlags(&g_upload_stream, hipStreamNonBlocking);
+  if (!g_upload_stream[device]) {
+    hipError_t e = hipStreamCreateWithFlags(&g_upload_stream[device], hipStreamNonBlocking);
     if (e != hipSuccess) return e;
   }
-  *out = g_upload_stream;
+  *out = g_upload_stream[device];
   return hipSuccess;
 }
 
@@ -104,8 +110,8 @@ void free_device(dbsp_device_plan& d) {
   if (d.uploaded) (void)hipEventSynchronize(static_cast<hipEvent_t>(d.uploaded));
   if (d.last_use) (void)hipEventDestroy(static_cast<hipEvent_t>(d.last_use));
   if (d.uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.uploaded));
-  pool_put(g_dev_pool, false, d.blob, d.blob_bytes);
-  pool_put(g_pin_pool, true, d.staging, d.staging_bytes);
+  pool_put(g_dev_pool, false, d.device, d.blob, d.blob_bytes);
+  pool_put(g_pin_pool, true, d.device, d.staging, d.staging_bytes);
   if (d.big_scratch) (void)hipFree(d.big_scratch);
   (void)hipGetLastError();
   d = dbsp_device_plan();
@@ -155,10 +161,10 @@ int upload(dbsp_plan* plan) {
   const size_t total = po_off + (size_t)rows * 128 * sizeof(float);
 
   void* blob = nullptr;
-  hipError_t e = pool_get(g_dev_pool, false, total, &blob, &dv.blob_bytes);
+  hipError_t e = pool_get(g_dev_pool, false, dv.device, total, &blob, &dv.blob_bytes);
   if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan device buffer: ") + hipGetErrorString(e)); }
   dv.blob = static_cast<unsigned char*>(blob);
-  e = pool_get(g_pin_pool, true, up_bytes, &dv.staging, &dv.staging_bytes);
+  e = pool_get(g_pin_pool, true, dv.device, up_bytes, &dv.staging, &dv.staging_bytes);
   if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan staging buffer: ") + hipGetErrorString(e)); }
 
   unsigned char* st = static_cast<unsigned char*>(dv.staging);
@@ -172,7 +178,7 @@ int upload(dbsp_plan* plan) {
   DBSP_HIP(hipEventCreateWithFlags(&ev_use, hipEventDisableTiming));
   dv.last_use = ev_use;
   hipStream_t us;
-  DBSP_HIP(upload_stream(&us));
+  DBSP_HIP(upload_stream(dv.device, &us));
   DBSP_HIP(hipMemcpyAsync(dv.blob, st, up_bytes, hipMemcpyHostToDevice, us));
   DBSP_HIP(hipEventRecord(ev_up, us));
 
@@ -305,6 +311,9 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
     return fail(DBSP_ESHAPE, "sparse_attn_fwd: Nq/Nk do not match the plan's block grid");
   if (!plan->dev.resident) return fail(DBSP_EINVAL, "sparse_attn_fwd: the plan was built host-only");
   if (!(softmax_scale == softmax_scale)) return fail(DBSP_EINVAL, "sparse_attn_fwd: softmax_scale is NaN");
+  int cur = -1;
+  DBSP_HIP(hipGetDevice(&cur));
+  if (cur != plan->dev.device) return fail(DBSP_EINVAL, "sparse_attn_fwd: the plan lives on another device than the current one");
   int rc = ensure_scratch(plan, B, d);
   if (rc != DBSP_OK) return rc;
 
