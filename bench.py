@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
 # HBM-side bytes per launch of dbsp_fwd_kernel (default placement), from rocprofv3 --pmc runs of this
 # command: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy
 # (see profiles/dbsp_fwd_kernel_wan480p_pmc.md).  Keyed by workload config; null when not measured.
-MEASURED_TRAFFIC = {3: 12.3e9}
+MEASURED_TRAFFIC = {3: 12.8e9}
 
 
 def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
@@ -124,8 +124,8 @@ def extras(dbsp, synth, torch, np, cfg, c, mask, q, k, v, o, lse):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="workload config (3 = Wan-14B-like 480p, the headline shape)")
     ap.add_argument("--partitions", type=int, default=0, help="0 = one per compute unit")
     ap.add_argument("--reuse-plan", action="store_true", help="static-mask mode: plan once outside the timed region")
