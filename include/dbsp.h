@@ -95,7 +95,8 @@ typedef struct dbsp_plan_opts {
  * scratch for split rows and busy-time capture.  The copy is asynchronous (a stream of the
  * library's own, pinned staging, buffers recycled from a process-wide pool): the call returns
  * without waiting for it, and sparse_attn_fwd makes its stream wait for the copy, so planning the
- * next call overlaps with the device's work on the current one.
+ * next call overlaps with the device's work on the current one.  Masks over 1 MB are counted and
+ * compacted on up to 8 host threads (joined before the call returns).
  * Errors: DBSP_EINVAL, DBSP_ENOMEM, DBSP_EHIP.  Rows with no active block are legal.
  */
 int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
