@@ -58,7 +58,7 @@ typedef struct dbsp_plan_opts {
                              the same time, so KV blocks are reused from L2: balance traded for locality,
                              the trade-off the paper steers with its reward factor R_b */
   int32_t max_item_len;   /* split threshold in blocks: a row with more active blocks is cut into
-                             ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (4 P)); < 0 -> never split */
+                             ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (2 P)); < 0 -> never split */
   int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
                              (rho_s is always computed from pure block counts). 0 = the paper's cost model */
   int32_t flags;          /* DBSP_PLAN_HOST_ONLY or 0 */

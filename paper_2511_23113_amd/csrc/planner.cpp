@@ -200,7 +200,7 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
 
     // split threshold
     int32_t L = max_item_len;
-    if (L == 0) L = (int32_t)std::max<int64_t>(4, hp.nnz / (4 * (int64_t)P));
+    if (L == 0) L = (int32_t)std::max<int64_t>(4, hp.nnz / (2 * (int64_t)P));   // half the mean partition load
     hp.max_item_len = L;
 
     // items in row-major order

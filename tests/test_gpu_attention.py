@@ -224,7 +224,7 @@ def test_plan_reuse_chain_on_the_config5_mask_sequence():
         if plan is None:
             plan = dbsp.plan_sparse_attn(mask, block, mode=dbsp.MODE_ROUNDS)
         else:
-            nxt, reused, rho = dbsp.plan_sparse_attn_reuse(plan, mask, 1.2, mode=dbsp.MODE_ROUNDS)
+            nxt, reused, rho = dbsp.plan_sparse_attn_reuse(plan, mask, 1.15, mode=dbsp.MODE_ROUNDS)
             plan.close()
             plan = nxt
             kept.append(reused)

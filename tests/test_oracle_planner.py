@@ -156,8 +156,8 @@ def test_make_items_split_rule():
     items, _, _ = op.make_items([1, 1, 1, 1], nQ=2, max_len=4)
     assert [(h, I) for h, I, _, _ in items] == [(0, 0), (0, 1), (1, 0), (1, 1)]
     assert op.auto_max_item_len(0, 256) == 4
-    assert op.auto_max_item_len(806283, 256) == 787
-    assert op.auto_max_item_len(56699, 256) == 55
+    assert op.auto_max_item_len(806283, 256) == 1574      # 806283 // 512: half the mean partition load
+    assert op.auto_max_item_len(56699, 256) == 110
 
 
 def _check_plan_invariants(mask, pl, overhead=0, rounds=False):
@@ -367,7 +367,7 @@ def test_calibration_by_hand_and_its_effect():
     tuned = op.plan(mask, 256, mode=op.MODE_BALANCED, partition_cost=cost)
     t_flat = [l * c for l, c in zip(flat["part_load"], cost)]
     t_tuned = [l * c for l, c in zip(tuned["part_load"], cost)]
-    assert max(t_tuned) / (sum(t_tuned) / 256) < 1.02 < max(t_flat) / (sum(t_flat) / 256)
+    assert max(t_tuned) / (sum(t_tuned) / 256) < 1.03 < max(t_flat) / (sum(t_flat) / 256)
     slow = [tuned["part_load"][g] for g in range(256) if g % 8 == 7]
     fast = [tuned["part_load"][g] for g in range(256) if g % 8 != 7]
     assert 0.93 < (sum(slow) / len(slow)) / (sum(fast) / len(fast)) < 0.97
