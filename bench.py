@@ -143,6 +143,9 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="also measure (extra launches, outside the timed region) kernel time against active-block count over the 50 "
                          "masks of config 5, and the memory rate of the low-density heads of this config run on their own")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="power experiment, not the benchmark: all-zero Q, K, V (same instruction stream and cycle count, far fewer "
+                         "bit flips, so the chip holds a higher clock)")
     ap.add_argument("--calibrate", action="store_true",
                     help="feed the per-compute-unit speeds measured in the last warm-up launch back into the placement "
                          "(worth about 1 %% once clocks have settled: use a long warm-up)")
@@ -171,6 +174,8 @@ def main():
     qb, kb, vb = synth.qkv_for_config(cfg, B, c["H"], c["Nq"], c["Nk"], d)
     dev = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
     q, k, v = dev(qb), dev(kb), dev(vb)
+    if args.zero_data:
+        q.zero_(), k.zero_(), v.zero_()
     o = torch.empty_like(q)
     lse = torch.empty((B, c["H"], c["Nq"]), dtype=torch.float32, device="cuda")
     nnz = int((mask != 0).sum())
@@ -311,7 +316,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if not args.zero_data else "synthetic, all-zero tensors (power experiment, not the benchmark)",
         "config": {"workload": f"config {cfg}: {c['name']} B={B} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={d} block={block}, "
                                f"nnz={nnz} active blocks (density {nnz / mask.size:.3f})",
                    "step": "plan_sparse_attn + sparse_attn_fwd" if static_plan is None else "sparse_attn_fwd (plan reused)",
@@ -329,7 +334,7 @@ def main():
                                                                           "unit": "1024 = mean time per block"},
                       **({"compare": side} if side else {})},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg) if (args.locality_groups == 8 and args.partitions == 0) else None,
+                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg) if (args.locality_groups == 8 and args.partitions == 0 and not args.zero_data) else None,
                      "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops,
                      **({"sustained_mfma_only": {**sustained, "frac_of_sustained": kern_tflops / sustained["mfma_tflops"]}}
                         if sustained else {})},
