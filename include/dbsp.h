@@ -151,8 +151,9 @@ int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, do
 /*
  * dbsp_mfma_probe -- the chip's sustained dense bf16 MFMA rate, measured on the spot (diagnostic: the
  * roofline's published peak assumes 2.4 GHz, the sustained rate shows what clock the chip holds).
- * Runs a kernel of back-to-back v_mfma_f32_32x32x16_bf16 (eight waves per compute unit) for a few
- * milliseconds on `stream` and synchronises.  tflops (required): achieved TFLOP/s; clock_ghz (may be
+ * Runs a kernel of back-to-back v_mfma_f32_32x32x16_bf16 on pseudo-random operands (eight waves per
+ * compute unit; the rate a chip sustains depends on how many bits flip) four times, about 10 ms each,
+ * on `stream`, synchronises and reports the last run.  tflops (required): achieved TFLOP/s; clock_ghz (may be
  * NULL): shader clock during the run.  Allocates and frees a small device buffer.
  * Errors: DBSP_EINVAL, DBSP_EHIP.
  */

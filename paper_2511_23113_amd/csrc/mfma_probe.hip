@@ -15,24 +15,42 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // Every wave issues `iters` x 8 independent v_mfma_f32_32x32x16_bf16 on four accumulators and
-// nothing else; two waves per SIMD keep the matrix pipe full.  Block 0 also reports the shader
-// clock it ran at (core cycles over ticks of the 100 MHz constant clock).
-__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, uint64_t* clocks, int iters, float seed) {
+// nothing else; two waves per SIMD keep the matrix pipe full.  The operands are eight different
+// register sets of pseudo-random values in [-2, 2) per lane (what the chip sustains depends on how
+// many bits flip, so constant operands would flatter it).  Block 0 also reports the shader clock
+// it ran at (core cycles over ticks of the 100 MHz constant clock).
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, uint64_t* clocks, int iters, uint32_t seed) {
   f32x16 acc[4];
   for (int a = 0; a < 4; ++a)
     for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
-  bf16x8 A, B;
-  for (int i = 0; i < 8; ++i) {
-    A[i] = (__bf16)(seed + (float)(threadIdx.x & 7));
-    B[i] = (__bf16)(seed * 0.5f);
-  }
+  bf16x8 A[8], B[8];
+#pragma unroll
+  for (int m = 0; m < 8; ++m)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t ha = mix32(seed + (blockIdx.x * 512u + threadIdx.x) * 131u + m * 17u + i);
+      const uint32_t hb = mix32(ha + 0x9e3779b9u);
+      A[m][i] = (__bf16)(((int)(ha & 0xffff) - 32768) * (1.0f / 16384.0f));
+      B[m][i] = (__bf16)(((int)(hb & 0xffff) - 32768) * (1.0f / 16384.0f));
+    }
   const uint64_t c0 = clock64(), w0 = wall_clock64();
+  float s = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int m = 0; m < 8; ++m) acc[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[m & 3], 0, 0, 0);
+    for (int m = 0; m < 8; ++m) acc[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m], B[m], acc[m & 3], 0, 0, 0);
+    if ((it & 63) == 63) {   // keep the sums finite (a few moves per 512 MFMAs)
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { s += acc[a][i]; acc[a][i] = 0.f; }
+    }
   }
   const uint64_t c1 = clock64(), w1 = wall_clock64();
-  float s = 0.f;
   for (int a = 0; a < 4; ++a)
     for (int i = 0; i < 16; ++i) s += acc[a][i];
   sink[blockIdx.x * blockDim.x + threadIdx.x] = s;
@@ -72,9 +90,10 @@ extern "C" int dbsp_mfma_probe(double* tflops, double* clock_ghz, void* stream) 
   if ((e = hipMalloc(&clocks, 2 * sizeof(uint64_t))) != hipSuccess) return failed(e);
   if ((e = hipEventCreate(&a)) != hipSuccess) return failed(e);
   if ((e = hipEventCreate(&b)) != hipSuccess) return failed(e);
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(grid), dim3(threads), 0, st, sink, clocks, 2000, 1.0f);   // warm-up
+  for (int rep = 0; rep < 3; ++rep)   // warm-up: clocks take a few tens of milliseconds to settle after idling
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(grid), dim3(threads), 0, st, sink, clocks, iters, 12345u + rep);
   if ((e = hipEventRecord(a, st)) != hipSuccess) return failed(e);
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(grid), dim3(threads), 0, st, sink, clocks, iters, 1.0f);
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(grid), dim3(threads), 0, st, sink, clocks, iters, 12345u);
   if ((e = hipGetLastError()) != hipSuccess) return failed(e);
   if ((e = hipEventRecord(b, st)) != hipSuccess) return failed(e);
   if ((e = hipEventSynchronize(b)) != hipSuccess) return failed(e);
