@@ -359,3 +359,31 @@ def test_mfma_probe_reports_a_plausible_sustained_rate():
     tflops, ghz = dbsp.mfma_probe()
     assert 800.0 < tflops < 2600.0            # below the 2.5 PFLOP/s nominal peak, far above anything but MFMA
     assert 1.0 < ghz < 2.6
+
+
+def test_two_batch_entries_at_full_size_share_the_plan():
+    # config 5 with B = 2 (different tensors per batch entry, one mask): the split-row scratch has to
+    # grow for the second entry, and every batch entry is checked on sampled rows, split ones included
+    import torch
+    import paper_2511_23113_amd as dbsp
+    c = synth.config_shape(5)
+    block, d, H, nQ = c["block"], c["d"], c["H"], c["nQ"]
+    mask = synth.mask_for_config(5)
+    qb, kb, vb = synth.qkv_for_config(5, 2, H, c["Nq"], c["Nk"], d)
+    plan, O, L = _run(mask, block, qb, kb, vb, mode=op.MODE_ROUNDS, locality_groups=8)
+    ref = op.plan(mask, plan.stats()["num_partitions"], mode=op.MODE_ROUNDS, locality_groups=8)
+    assert len(ref["split_rows"]) > 0
+    rows = []
+    for b in (0, 1):
+        rows += [(b, int(h), int(I)) for h, I in ((0, 3), (4, 77), (9, 127))]
+        for r, _, _ in ref["split_rows"][:3]:
+            rows.append((b, r // nQ, r % nQ))
+    q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    Or, Lr = oa.masked_attention_rows(q32, k32, v32, mask, block, rows)
+    O = O.reshape(2, H, nQ, block, d)
+    L = L.reshape(2, H, nQ, block)
+    for t, (b, h, I) in enumerate(rows):
+        assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL, (b, h, I)
+        assert np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL, (b, h, I)
+    assert np.isfinite(O).all() and not np.array_equal(O[0], O[1])
+    plan.close()
