@@ -59,28 +59,23 @@ def biased_greedy(counts, groups: int, reward: float = 0.0, initial=None, capaci
     n = len(counts)
     if capacity and capacity * groups < n:
         raise ValueError("capacity too small to hold every unit")
-    order = sorted(range(n), key=lambda j: -int(counts[j]))
-    loads = [0] * groups
-    held = [0] * groups
+    load = np.zeros(groups, dtype=np.int64)
+    units = np.zeros(groups, dtype=np.int64)
     where = [0] * n
     lists = [[] for _ in range(groups)]
-    for j in order:
+    for j in sorted(range(n), key=lambda u: -int(counts[u])):          # descending, stable
         w = int(counts[j])
-        best, best_val = -1, 0.0
-        for g in range(groups):
-            if capacity and held[g] >= capacity:
-                continue
-            val = float(loads[g])
-            if initial is not None and reward != 0.0 and g == initial[j]:
-                bonus = float(reward) * float(w)
-                val = val - bonus
-            if best < 0 or val < best_val:
-                best, best_val = g, val
-        where[j] = best
-        lists[best].append(j)
-        loads[best] += w
-        held[best] += 1
-    return where, lists, loads
+        biased = load.astype(np.float64)                               # what the argmin looks at
+        if initial is not None and reward != 0.0:
+            biased[initial[j]] -= float(reward) * float(w)             # the unit's own GPU looks emptier
+        if capacity:
+            biased[units >= capacity] = np.inf                         # full GPUs are out
+        g = int(np.argmin(biased))                                     # first minimum: lowest index on ties
+        where[j] = g
+        lists[g].append(j)
+        load[g] += w
+        units[g] += 1
+    return where, lists, [int(v) for v in load]
 
 
 def partition_heads(blocks_per_head, x: int, capacity: int = 0, previous=None, reuse_threshold: float = 1.0):

@@ -29,8 +29,6 @@ Readings where the paper is silent or garbled (all integer rules):
 
 from __future__ import annotations
 
-import heapq
-
 import numpy as np
 
 MODE_BALANCED = 0
@@ -118,13 +116,12 @@ def lpt_partition(weights, P: int, cost=None):
     paper's rule."""
     cost = [1] * P if cost is None else [int(x) for x in cost]
     order = sorted(range(len(weights)), key=lambda i: -weights[i])   # Python's sort is stable
-    heap = [(0, g) for g in range(P)]                                # (time, index): lowest index wins ties
-    heapq.heapify(heap)
+    time = np.zeros(P, dtype=np.int64)                               # accumulated time per partition
     assign = [0] * len(weights)
     for i in order:
-        t, g = heapq.heappop(heap)
+        g = int(np.argmin(time))                                     # first minimum: lowest index wins ties
         assign[i] = g
-        heapq.heappush(heap, (t + weights[i] * cost[g], g))
+        time[g] += int(weights[i]) * cost[g]
     loads = [0] * P
     for i, g in enumerate(assign):
         loads[g] += weights[i]

@@ -37,16 +37,11 @@ def _run(mask, block, qb, kb, vb, scale=0.0, want_lse=True, **plan_kw):
     return plan, _host_f32(o), (lse.cpu().numpy() if lse is not None else None)
 
 
-def _check_all_rows(mask, block, qb, kb, vb, O, L, scale=None, relative_above_one=False):
+def _check_all_rows(mask, block, qb, kb, vb, O, L, scale=None):
     q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
     Or, Lr = oa.masked_attention(q32, k32, v32, mask, block, scale=scale)
     assert np.isfinite(O).all()
-    if relative_above_one:
-        # outputs of magnitude 2..4 carry a bf16 rounding error of up to 2^-7 by themselves: the
-        # absolute bound is applied to |O| <= 1 and scaled with |O| beyond
-        assert (np.abs(O - Or) <= O_TOL * np.maximum(1.0, np.abs(Or))).all()
-    else:
-        assert np.abs(O - Or).max() <= O_TOL
+    assert np.abs(O - Or).max() <= O_TOL
     if L is not None:
         empty = np.isneginf(Lr)
         assert np.array_equal(np.isneginf(L), empty)
@@ -141,7 +136,7 @@ def _sample_rows(mask, per_head, seed):
     return sorted(rows)
 
 
-@pytest.mark.parametrize("cfg,per_head", [(2, 2), (3, 2), (5, 4), (4, 1)])
+@pytest.mark.parametrize("cfg,per_head", [(2, 2), (3, 2), (5, 4), (4, 2)])
 def test_full_size_configs_sampled_rows(cfg, per_head):
     # the launch configuration the benchmark times: default partitions, round-based placement with
     # one locality group per XCD
@@ -177,6 +172,26 @@ def test_full_size_configs_sampled_rows(cfg, per_head):
     busy, hw = plan.busy()
     assert busy.shape == (st["num_partitions"],) and (busy > 0).sum() >= min(st["num_partitions"], st["n_items"]) * 0.99
     plan.close()
+
+
+def test_config5_all_rows_in_the_benchmark_placement_and_the_greedy_one():
+    # every row of one full-size config-5 mask (1,280 rows, split rows and all 256 partitions
+    # included) against the oracle evaluated in float32, in the placement the benchmark times and in
+    # the paper's plain greedy
+    c = synth.config_shape(5)
+    block, d = c["block"], c["d"]
+    mask = synth.mask_for_config(5)
+    qb, kb, vb = synth.qkv_for_config(5, c["B"], c["H"], c["Nq"], c["Nk"], d)
+    q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    Or, Lr = oa.masked_attention(q32, k32, v32, mask, block, dtype=np.float32)
+    assert np.isfinite(Lr).all()
+    for kw in (dict(mode=op.MODE_ROUNDS, locality_groups=8), dict(mode=op.MODE_BALANCED)):
+        plan, O, L = _run(mask, block, qb, kb, vb, **kw)
+        st = plan.stats()
+        assert st["n_items"] > c["H"] * c["nQ"]              # some rows are split
+        assert np.abs(O - Or).max() <= O_TOL, kw
+        assert np.abs(L - Lr).max() <= LSE_TOL, kw
+        plan.close()
 
 
 def test_replanning_every_call_on_the_config5_mask_sequence():
@@ -318,8 +333,12 @@ def test_calibrated_placement_matches_the_oracle_and_evens_out_busy_time():
     for _ in range(2):
         o, lse = dbsp.sparse_attn_fwd(tuned, q, k, v)
     t1, _ = tuned.busy()
-    spread0, spread1 = float(t0.max() / t0.mean()), float(t1.max() / t1.mean())
-    assert spread1 <= spread0 + 0.03        # rates move a little with the load and from launch to launch
+    # what the calibrated greedy promises is balance of the cost-weighted load it was given (measured
+    # rates move with the load and from launch to launch, so the measured spread is only kept sane)
+    load1 = tuned.array(B.PART_LOAD)
+    time0, time1 = load0 * cost.astype(np.int64), load1 * cost.astype(np.int64)
+    assert time1.max() / time1.mean() <= max(time0.max() / time0.mean(), 1.02)
+    assert 1.0 <= float(t1.max() / t1.mean()) < 1.5
     rows = [(0, h, I) for h, I in ((0, 0), (3, 17), (9, 127), (5, 64))]
     q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
     Or, Lr = oa.masked_attention_rows(q32, k32, v32, mask, block, rows)
@@ -342,7 +361,7 @@ def test_scores_that_keep_growing_take_the_rescale_path(block, d):
     rng = np.random.default_rng(99)
     q = rng.standard_normal((B_, H, nQ * block, d)).astype(np.float32)
     k = rng.standard_normal((B_, H, nK * block, d)).astype(np.float32)
-    v = rng.standard_normal((B_, H, nK * block, d)).astype(np.float32)
+    v = rng.uniform(-1.0, 1.0, (B_, H, nK * block, d)).astype(np.float32)   # |O| <= 1: the absolute bound applies as it stands
     k *= np.linspace(0.2, 6.0, nK * block, dtype=np.float32)[None, None, :, None]      # growth along the keys
     k[:, :, rng.integers(0, nK * block, 12)] *= 4.0                                     # outliers
     q[:, :, 5] = 1e-3 * q[:, :, 5]                                                      # a flat row
@@ -350,7 +369,7 @@ def test_scores_that_keep_growing_take_the_rescale_path(block, d):
     for kw in (dict(num_partitions=4), dict(num_partitions=5, max_item_len=2)):
         plan, O, L = _run(mask, block, qb, kb, vb, **kw)
         # scores reach a few hundred here: O stays a convex combination of V rows, LSE is large
-        _check_all_rows(mask, block, qb, kb, vb, O, L, relative_above_one=True)
+        _check_all_rows(mask, block, qb, kb, vb, O, L)
         plan.close()
 
 

@@ -1,6 +1,6 @@
 """Pins for the multi-GPU planner oracle (oracle/dual_balance.py): hand-traced runs of the greedy
-with and without reward and capacity, a second independent greedy (the heap-based one of the
-single-GPU oracle), the classical 4/3 - 1/(3m) bound against a brute-force optimum, brute-force
+with and without reward and capacity, a second independent greedy (a priority-queue one written in the test), a step-by-step replay of
+the placement rule, the classical 4/3 - 1/(3m) bound against a brute-force optimum, brute-force
 ring work on tiny masks, and the special cases whose rho_s is known in closed form."""
 
 import itertools
@@ -70,15 +70,51 @@ def test_reward_by_hand():
     assert where == init and loads == [8, 4]
 
 
-def test_unbiased_greedy_equals_the_heap_based_greedy():
-    # two separately written implementations of the same rule (linear argmin here, heap there)
+def _heap_greedy(w, g):
+    # the same rule written a second way: a priority queue of (load, bin) instead of a scan
+    import heapq
+    heap = [(0, b) for b in range(g)]
+    where = [0] * len(w)
+    for j in sorted(range(len(w)), key=lambda u: (-w[u], u)):
+        load, b = heapq.heappop(heap)
+        where[j] = b
+        heapq.heappush(heap, (load + w[j], b))
+    return where
+
+
+def test_unbiased_greedy_equals_a_priority_queue_greedy():
     rng = np.random.default_rng(1)
     for _ in range(200):
         n, g = int(rng.integers(0, 40)), int(rng.integers(1, 9))
         w = rng.integers(0, 30, n).tolist()
         where, _, loads = db.biased_greedy(w, g)
         assign, loads2 = op.lpt_partition(w, g)
-        assert where == assign and loads == loads2
+        assert where == assign == _heap_greedy(w, g) and loads == loads2
+
+
+def test_every_unit_lands_on_the_smallest_biased_load_among_open_bins():
+    # replay the returned placement in the order it was made (descending count, stable) and check
+    # the rule itself at every step: among bins that are not full, none had a smaller load after
+    # crediting the unit's home bin with reward * count, and no lower-indexed bin had an equal one
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        g = int(rng.integers(1, 6))
+        n = int(rng.integers(0, 14))
+        cap = int(rng.integers(0, 5))
+        if cap and cap * g < n:
+            cap = 0
+        w = rng.integers(0, 12, n).tolist()
+        home = rng.integers(0, g, n).tolist()
+        reward = float(rng.choice([0.0, 0.25, 0.6, 1.0, 3.0]))
+        where, lists, loads = db.biased_greedy(w, g, reward, home, cap)
+        load, held = [0] * g, [0] * g
+        for j in sorted(range(n), key=lambda u: (-w[u], u)):
+            seen = {b: load[b] - (reward * w[j] if b == home[j] else 0.0) for b in range(g) if not cap or held[b] < cap}
+            lowest = min(seen.values())
+            assert where[j] == min(b for b, val in seen.items() if val == lowest), (w, home, reward, cap, j)
+            load[where[j]] += w[j]
+            held[where[j]] += 1
+        assert load == loads and [sorted(l) for l in lists] == [sorted(j for j in range(n) if where[j] == b) for b in range(g)]
 
 
 def _optimal_makespan(w, g):
