@@ -29,18 +29,22 @@
 //     the MFMAs of  K Q^T of unit i   and of  V^T P^T of unit i-2,  and
 //     the VALU work of the softmax of unit i-1,
 //   so matrix and vector pipes run side by side inside one instruction stream (and across the
-//   two waves of a SIMD); S and P are double buffered in registers.  The softmax is speculative:
-//   probabilities are formed against the running max as it stands; only when a score exceeds it
-//   by more than 2^RESCALE_LOG2 is the unit redone with a raised max and the accumulator rescaled.
-//   The steady state is unrolled over two KV blocks, so LDS buffer offsets are immediates.
+//   two waves of a SIMD); S and P are double buffered in registers.  A step is a sequence of
+//   slots (one V^T P^T MFMA, one K Q^T MFMA, the softmax of two scores per lane, three LDS reads)
+//   fenced from each other, and the LDS operands of a slot are read eight MFMAs earlier (those
+//   of a step's first half during the step before), so no MFMA waits for a read issued right
+//   before it.  The softmax is speculative: probabilities are formed against the running max as
+//   it stands; only when a unit's per-lane sum of probabilities exceeds SPEC_SUM_LIMIT (some
+//   score is far above the running max) is the unit redone with a raised max and the accumulator
+//   rescaled.  The steady state is unrolled over two KV blocks, so LDS buffer offsets are immediates.
 // At full occupancy of the chip the kernel runs power-limited (the shader clock drops to about
 // 1.8 GHz with all 256 compute units busy, 2.4 GHz with half of them), so instructions and
 // bytes saved count as much as cycles saved.
 // Data movement:
 //   * K and V blocks go L2 -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
-//     VGPR staging), double buffered; each step issues one group of copies per tensor, behind
-//     MFMAs that are already queued (every inline-asm statement is a scheduling boundary for the
-//     compiler, so few groups beat many single copies).
+//     VGPR staging), double buffered.  There is one barrier per KV block, in the middle of the
+//     block's second step; right behind it K of the block after next and V of the next block are
+//     copied into the two buffers that barrier retires, so a copy has two steps to land.
 //   * LDS tiles are unpadded; 16-byte chunks are XOR-swizzled inside each row instead (the
 //     permutation is applied to the per-lane global source address, the LDS side of the copy
 //     is linear): K by the row index so that the 16-byte operand reads of 16 lanes (16
@@ -65,8 +69,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// the running max is raised only when a query's max grows by more than this many powers of two
-constexpr float RESCALE_LOG2 = 6.0f;
+// The speculative softmax redoes a unit when a lane's sum of its 16 probabilities exceeds this:
+// then some score is above the running max by about six powers of two or more (16 probabilities
+// at or below 1 sum to less than the limit; until it trips, P may exceed 1 by at most this
+// factor, which f32 / bf16 hold without loss).
+constexpr float SPEC_SUM_LIMIT = 64.0f;
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
@@ -137,7 +144,6 @@ struct Cfg {
   static constexpr int ROW_BYTES = D * 2;
   static constexpr int TILE_BYTES = BLK * D * 2;
   static constexpr int LOADS = (BLK * D / 8 / 64) / NW;   // 1-KiB direct-to-LDS copies per wave per tile
-  static constexpr int CP = LOADS / U;                    // copies of each tensor per pipeline step (one group)
   static constexpr int RPC = 64 / NCH;                    // tile rows per copy
   // K's swizzle has period NCH*RPL rows: consecutive copies cycle through KVAR per-lane source offsets
   static constexpr int KVAR = (NCH * RPL) / RPC;
@@ -203,7 +209,7 @@ void dbsp_fwd_kernel(
     for (int dt = 0; dt < C::DT; ++dt) {
       // V's region offset is part of the per-lane base (kept opaque), so that buffer, unit and
       // k-step offsets of a read fit the instruction's 16-bit immediate
-      v_rd[dt] = V_OFF + key * C::ROW_BYTES + ((((4 * dt) ^ sw) + 2 * hh + (a4 >> 1)) << 4) + (a4 & 1) * 8;
+      v_rd[dt] = lds_base + V_OFF + key * C::ROW_BYTES + ((((4 * dt) ^ sw) + 2 * hh + (a4 >> 1)) << 4) + (a4 & 1) * 8;
       asm volatile("" : "+v"(v_rd[dt]));
     }
   }
@@ -226,16 +232,32 @@ void dbsp_fwd_kernel(
 
       // byte offset of this wave's share inside a tile, same in global memory and in LDS
       const uint32_t wave_off = w * C::LOADS * 1024;
-      // K of the first block; V of block T is copied during block T's steps
+      // one wave's share of a tile: LOADS copies of 1 KiB, in groups of four that share an M0 and a base
+      auto copy_k_tile = [&](int J, int buf) {
+        const unsigned char* from = kbase + (int64_t)J * C::TILE_BYTES + wave_off;
+        const uint32_t to = lds_base + K_OFF + buf * C::TILE_BYTES + wave_off;
 #pragma unroll
-      for (int grp = 0; grp < C::U; ++grp) {
-        const uint32_t off = wave_off + grp * C::CP * 1024;
-#pragma unroll
-        for (int n = 0; n < C::CP; ++n) {
-          if (n % 4 == 0) set_copy_dst(lds_base + K_OFF + off + n * 1024);
-          copy16_nth(n % 4, kbase + (int64_t)kv[0] * C::TILE_BYTES + off + (n / 4) * 4096, k_src[(grp * C::CP + n) % C::KVAR]);
+        for (int n = 0; n < C::LOADS; ++n) {
+          if (n % 4 == 0) set_copy_dst(to + n * 1024);
+          copy16_nth(n % 4, from + (n / 4) * 4096, k_src[n % C::KVAR]);
         }
-      }
+      };
+      auto copy_v_tile = [&](int J, int buf) {
+        const unsigned char* from = vbase + (int64_t)J * C::TILE_BYTES + wave_off;
+        const uint32_t to = lds_base + V_OFF + buf * C::TILE_BYTES + wave_off;
+#pragma unroll
+        for (int n = 0; n < C::LOADS; ++n) {
+          if (n % 4 == 0) set_copy_dst(to + n * 1024);
+          copy16_nth(n % 4, from + (n / 4) * 4096, v_src);
+        }
+      };
+      // Tile schedule: K and V of block T live in buffer T & 1.  K of blocks 0 and 1 and V of block
+      // 0 are copied here; from then on the barrier in the middle of block T's second step is
+      // followed by the copies of K of block T+2 and V of block T+1, into the buffers whose last
+      // reads that barrier has just retired: every copy has two steps to land.
+      copy_k_tile(kv[0], 0);
+      if (n_tiles > 1) copy_k_tile(kv[1], 1);
+      copy_v_tile(kv[0], 0);
 
       // Q^T operands of this wave's 64 queries: lane (r, g) holds q[32*qt + r][16ks + 8g .. +7]
       const int q0 = 32 * C::QT * wa;
@@ -249,8 +271,9 @@ void dbsp_fwd_kernel(
       }
       // Make the compiler wait for the Q loads here, before the loop, rather than at their first use
       // inside it (a wait inside the loop would also wait for the in-flight tile copies: same
-      // counter).  With eight waves (two per SIMD, 256 registers each) nothing lives in accumulation
-      // registers: every MFMA reads and writes the arch-VGPR file and the softmax reads S in place.
+      // counter; the copies above were issued first, so this wait covers them too).  With eight
+      // waves (two per SIMD, 256 registers each) nothing lives in accumulation registers: every MFMA
+      // reads and writes the arch-VGPR file and the softmax reads S in place.
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
@@ -266,113 +289,115 @@ void dbsp_fwd_kernel(
         for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
           for (int i = 0; i < 16; ++i) oacc[dt][qt][i] = 0.f;
-      float m_run[C::QT], l_run[C::QT];
+      float m_run[C::QT], mc_run[C::QT], l_run[C::QT];   // running max, the same times scale*log2(e), running sum
 #pragma unroll
-      for (int qt = 0; qt < C::QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
+      for (int qt = 0; qt < C::QT; ++qt) { m_run[qt] = mc_run[qt] = -INFINITY; l_run[qt] = 0.f; }
 
       // double-buffered pipeline registers: S[x] = scores of the unit whose K Q^T ran in a step of
       // parity x; Pb[x] = its probabilities, packed to bf16 as the B operands of two 16-key steps
       f32x16 S[2][C::QT];
       bf16x8 Pb[2][2][C::QT];
+      // The LDS operands of the first half of a step's MFMAs are read during the second half of the
+      // step before, those of the second half during the first half: no MFMA waits for a read
+      // issued right before it.
+      constexpr int KH = C::KS_QK / 2;
+      bf16x8 kaA[KH];          // K rows of the next K Q^T unit, k-steps [0, KH)
+      s16x4 vaA[C::DT][2];     // V^T operands of the next V^T P^T unit, first 16-key step
 
-      int j_cur = kv[0], j_nxt = kv[(1 < n_tiles) ? 1 : 0], j_pre = kv[(2 < n_tiles) ? 2 : n_tiles - 1];
+      // LDS reads.  K: rows of `half` of the block in buffer `buf`, k-step ks.  V: 16-key step ks of
+      // `half` of the block in buffer `buf`, d-tile dt (two transposing reads)
+      auto read_k = [&](int buf, int half, int ks) {
+        const unsigned char* sK = lds + K_OFF + buf * C::TILE_BYTES + half * 32 * C::ROW_BYTES;
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(sK + (k_rd0 ^ (ks << 5))));
+      };
+      auto read_v = [&](s16x4 (&dst)[2], int buf, int half, int ks, int dt) {
+        // absolute LDS byte address as an integer: per-lane base (LDS base and V_OFF inside) plus an
+        // offset that is an immediate whenever the buffer parity is static
+        const uint32_t vp = v_rd[dt] + buf * C::TILE_BYTES + half * 32 * C::ROW_BYTES + ks * 16 * C::ROW_BYTES;
+        dst[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)(vp));
+        dst[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)(vp + 8 * C::ROW_BYTES));
+      };
 
-      // One pipeline step.  PAR = parity of the step; QK / SM / PV say which stages are live
-      // (all three in the steady state; fewer while the pipeline fills and drains).
-      auto step = [&](int i, auto par_tag, auto qk_tag, auto sm_tag, auto pv_tag, auto buf_tag) {
+      // id of the block whose V is copied after the next barrier (the block whose K went last)
+      int j_v = kv[(1 < n_tiles) ? 1 : 0];
+
+      // One pipeline step.  PAR = parity of the step = half of the KV block its K Q^T unit covers;
+      // QK / SM / PV say which stages are live (all three in the steady state; fewer while the
+      // pipeline fills and drains); NQK / NPV say the same of the next step, whose first operands
+      // this step reads.  The step is a sequence of slots -- two MFMAs, the softmax of two (or
+      // four) scores per lane, three LDS reads -- fenced off from each other, so that the matrix
+      // pipe always has work queued while the vector work of both waves of a SIMD issues,
+      // whatever the phase between the two waves.
+      auto step = [&](int i, auto par_tag, auto qk_tag, auto sm_tag, auto pv_tag, auto buf_tag, auto nqk_tag, auto npv_tag) {
         constexpr int PAR = decltype(par_tag)::value;
         // BUF = parity of the KV block of the K Q^T stage when it is known at compile time (steady
         // state: every LDS address is then a loop-invariant register plus an immediate), else -1
         constexpr int BUF = decltype(buf_tag)::value;
         constexpr bool QK = decltype(qk_tag)::value, SM = decltype(sm_tag)::value, PV = decltype(pv_tag)::value;
-        // with two units per KV block the step parity is also the unit's half of the block
-        constexpr int HALF = (C::U == 1) ? 0 : PAR;
-        const int Tq = i / C::U, hq = HALF;                  // unit of the K Q^T stage
-        const int Tp = (i - 2) / C::U, hp = HALF;            // unit of the V^T P^T stage
+        constexpr bool NQK = decltype(nqk_tag)::value, NPV = decltype(npv_tag)::value;
+        constexpr int HALF = PAR, NHALF = 1 - PAR;
+        const int Tq = i / C::U;                             // block of the K Q^T stage's unit
+        const int Tp = (i - 2) / C::U;                       // block of the V^T P^T stage's unit
         static_assert(C::NKB == 2 && C::NVB == 2, "buffer parities below assume double buffering");
-        const int bq = (BUF >= 0) ? BUF : (Tq & 1);          // buffer of block Tq (K read, V copy)
-        const int bp = (BUF >= 0) ? 1 - BUF : (Tp & 1);      // buffer of block Tp = Tq - 1 (V read)
-        if (C::U == 1 || PAR == 0) {
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's copies issued so far have landed
-          __syncthreads();   // ... and everybody's; every wave is past the steps that read the buffers refilled next
-        }
-        // tile copies of this step: K of block Tq+1 (clamped at the end: one redundant copy per
-        // item) and V of block Tq, split over the U steps of block Tq
-        // block ids come from scalar loads issued one KV block ahead (j_cur = kv[Tq], j_nxt = kv[Tq+1],
-        // clamped), so that no step waits for the scalar cache
-        if (HALF == 0 && i > 0) {
-          j_cur = j_nxt;
-          j_nxt = j_pre;
-          j_pre = kv[(Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1];
-        }
-        const int Jk = j_nxt, Jv = j_cur;
-        // this step's group of copies: [HALF*CP, HALF*CP + CP) of the wave's share of each tile
-        constexpr int CP = C::CP;
-        const uint32_t grp_off = wave_off + HALF * CP * 1024;
-        const unsigned char* k_from = kbase + (int64_t)Jk * C::TILE_BYTES + grp_off;
-        const unsigned char* v_from = vbase + (int64_t)Jv * C::TILE_BYTES + grp_off;
-        const uint32_t k_to = lds_base + K_OFF + (1 - bq) * C::TILE_BYTES + grp_off;
-        const uint32_t v_to = lds_base + V_OFF + bq * C::TILE_BYTES + grp_off;
-        // copies are grouped in fours: one M0 write and one base per group, instruction offsets inside
-        auto copy_k = [&](int n) {
-          if (n % 4 == 0) set_copy_dst(k_to + n * 1024);
-          copy16_nth(n % 4, k_from + (n / 4) * 4096, k_src[(HALF * CP + n) % C::KVAR]);
-        };
-        auto copy_v = [&](int n) {
-          if (n % 4 == 0) set_copy_dst(v_to + n * 1024);
-          copy16_nth(n % 4, v_from + (n / 4) * 4096, v_src);
-        };
+        const int bq = (BUF >= 0) ? BUF : (Tq & 1);          // buffer of block Tq
+        const int bp = (BUF >= 0) ? 1 - BUF : (Tp & 1);      // buffer of block Tp = Tq - 1
+        // next step: its K Q^T unit is the other half of block Tq, or the first half of block Tq+1;
+        // its V^T P^T unit is the other half of block Tp, or the first half of block Tp+1
+        const int nbq = (HALF == 0) ? bq : 1 - bq, nbp = (HALF == 0) ? bp : 1 - bp;
 
-        // LDS operand reads of this step
-        bf16x8 ka[C::KS_QK];
-        const unsigned char* sK = lds + K_OFF + bq * C::TILE_BYTES + hq * 32 * C::ROW_BYTES;
-        constexpr int PF_K = C::KS_QK / 2;   // K operand reads run this many k-steps ahead of their MFMAs
-        auto read_k = [&](int ks) { ka[ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(sK + (k_rd0 ^ (ks << 5)))); };
-        if constexpr (QK) {
+        bf16x8 kaB[KH];
+        s16x4 vaB[C::DT][2];
+
+        // ---- softmax of unit i-1 (VALU), reading S[1-PAR], writing Pb[1-PAR], in eight chunks of
+        // two scores.  Speculative: probabilities are formed against the running max as it stands,
+        // which is right unless some score is far above it (see SPEC_SUM_LIMIT).
+        bool pend = false;
+        float l_spec[C::QT], ls0[C::QT], ls1[C::QT];
+        uint32_t pw[C::QT][4];
+        auto softmax_chunk = [&](int j) {     // j = 0..7: scores 2j and 2j+1 of every tile
+          const int hf = j / 4, e2 = j % 4;
 #pragma unroll
-          for (int ks = 0; ks < PF_K; ++ks) read_k(ks);
-        }
-        s16x4 va[2][C::DT][2];
-        const unsigned char* sV = lds + bp * C::TILE_BYTES + hp * 32 * C::ROW_BYTES;   // V_OFF is inside v_rd
-        auto read_v = [&](int ks) {
-#pragma unroll
-          for (int dt = 0; dt < C::DT; ++dt) {
-            const unsigned char* vp = sV + v_rd[dt] + ks * 16 * C::ROW_BYTES;
-            va[ks][dt][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(vp));
-            va[ks][dt][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(vp + 8 * C::ROW_BYTES));
+          for (int qt = 0; qt < C::QT; ++qt) {
+            const f32x16& sv = S[1 - PAR][qt];
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc_run[qt]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc_run[qt]));
+            if (j == 0) { ls0[qt] = p0; ls1[qt] = p1; }      // no "0 + p" to start the two chains
+            else { ls0[qt] += p0; ls1[qt] += p1; }
+            pw[qt][e2] = pack_bf16x2(p0, p1);
+            if (e2 == 3) {
+              const u32x4 pb = {pw[qt][0], pw[qt][1], pw[qt][2], pw[qt][3]};
+              Pb[1 - PAR][hf][qt] = as_bf16x8(pb);
+            }
+            if (j == 7) {
+              // The test costs one compare (+inf from a running max of -inf, the first unit of an
+              // item, trips it too).  Any lane's excess sends the whole wave to the slow path.
+              const float lsum = ls0[qt] + ls1[qt];
+              pend = pend || (__builtin_amdgcn_ballot_w64(lsum > SPEC_SUM_LIMIT) != 0);
+              l_spec[qt] = l_run[qt] + lsum;
+            }
           }
         };
-        if constexpr (PV) read_v(0);
-
-        // ---- softmax of unit i-1 (VALU), reading S[1-PAR], writing Pb[1-PAR] --------------
-        // Speculative: probabilities are formed against the running max as it stands, which is
-        // right unless some score exceeds it by more than 2^RESCALE_LOG2 (in exp2 units; until
-        // then P may exceed 1 by at most that factor, which f32 / bf16 hold without loss).  The
-        // test needs no cross-lane exchange (any lane's excess sends the whole wave to the slow
-        // path below), so the common path pays neither the row-max exchange nor a rescale factor.
-        bool pend = false;
-        float l_spec[C::QT];
-        // p = exp2(s*c - mc) for the 16 scores of tile qt, packed to bf16 into Pb; returns their sum
+        // slow path: p = exp2(s*c - mc) for the 16 scores of tile qt, packed to bf16 into Pb; returns their sum
         auto probabilities = [&](int qt, float mc) {
           const f32x16& sv = S[1 - PAR][qt];
-          float ls0 = 0.f, ls1 = 0.f;
+          float a0 = 0.f, a1 = 0.f;
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {
-            uint32_t pw[4];
+            uint32_t w4[4];
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) {
               const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc));
               const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc));
-              ls0 += p0;
-              ls1 += p1;
-              pw[e2] = pack_bf16x2(p0, p1);
+              a0 += p0;
+              a1 += p1;
+              w4[e2] = pack_bf16x2(p0, p1);
             }
-            const u32x4 pb = {pw[0], pw[1], pw[2], pw[3]};
+            const u32x4 pb = {w4[0], w4[1], w4[2], w4[3]};
             Pb[1 - PAR][hf][qt] = as_bf16x8(pb);
           }
-          return ls0 + ls1;
+          return a0 + a1;
         };
-        // largest of this lane's 16 scores of tile qt: two chains of 3-input maxima
+        // slow path: largest of this lane's 16 scores of tile qt, two chains of 3-input maxima
         auto lane_max = [&](int qt) {
           const f32x16& sv = S[1 - PAR][qt];
           float mx0 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), mx1 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);
@@ -383,63 +408,79 @@ void dbsp_fwd_kernel(
           mx0 = fmaxf(fmaxf(mx0, sv[14]), sv[15]);
           return fmaxf(mx0, mx1);
         };
-        if constexpr (SM) {
-#pragma unroll
-          for (int qt = 0; qt < C::QT; ++qt) {
-            const float over = (lane_max(qt) - m_run[qt]) * c;
-            pend = pend || (__builtin_amdgcn_ballot_w64(over > RESCALE_LOG2) != 0);
-            l_spec[qt] = l_run[qt] + probabilities(qt, m_run[qt] * c);
-          }
-        }
 
-        // ---- MFMA work: V^T P^T of unit i-2 (operands read above) and K Q^T of unit i ------
-        if constexpr (PV) {
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks) {
-            if (ks == 0) read_v(1);
-#pragma unroll
-            for (int dt = 0; dt < C::DT; ++dt) {
-              const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[ks][dt][0], va[ks][dt][1], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-              for (int qt = 0; qt < C::QT; ++qt)
-                oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[PAR][ks][qt], oacc[dt][qt], 0, 0, 0);
-              if constexpr (QK) {   // this step's K copies, as one group behind the first MFMAs
-                if (ks == 0 && dt == 1) {
-#pragma unroll
-                  for (int n = 0; n < CP; ++n) copy_k(n);
-                }
-              }
-            }
-          }
-        }
-        if constexpr (QK) {
-          if constexpr (!PV) {
-#pragma unroll
-            for (int n = 0; n < CP; ++n) copy_k(n);
-          }
+        auto mfma_pv = [&](const s16x4 (&va)[2], int ks, int dt) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[0], va[1], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt)
+            oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[PAR][ks][qt], oacc[dt][qt], 0, 0, 0);
+        };
+        auto mfma_qk = [&](const bf16x8& ka, int ks) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) S[PAR][qt][e] = 0.f;
+          for (int qt = 0; qt < C::QT; ++qt) {
+            if (ks == 0) {
 #pragma unroll
-          for (int ks = 0; ks < C::KS_QK; ++ks) {
-            if (ks + PF_K < C::KS_QK) read_k(ks + PF_K);
-#pragma unroll
-            for (int qt = 0; qt < C::QT; ++qt)
-              S[PAR][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qt][ks], S[PAR][qt], 0, 0, 0);
-            if (ks == 1) {   // this step's V copies, as one group behind the first MFMAs
-#pragma unroll
-              for (int n = 0; n < CP; ++n) copy_v(n);
+              for (int e = 0; e < 16; ++e) S[PAR][qt][e] = 0.f;
             }
+            S[PAR][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qt][ks], S[PAR][qt], 0, 0, 0);
           }
-          static_assert(C::KS_QK >= CP && 2 * C::DT >= CP, "not enough MFMA slots to spread the copies over");
+        };
+        // a half step holds DT d-tiles of V^T P^T and KH k-steps of K Q^T (DT == KH): slot x pairs them
+        static_assert(C::DT == KH, "a slot pairs one d-tile of V^T P^T with one k-step of K Q^T");
+        constexpr int SLOTS = KH, CPS = 4 / SLOTS;     // softmax chunks per slot
+        static_assert(SLOTS * CPS == 4, "four softmax chunks per half step");
+
+        // ---- first half: MFMAs on the operands read during the previous step; reads for the second half
+        int jk = 0;
+#pragma unroll
+        for (int x = 0; x < SLOTS; ++x) {
+          if constexpr (QK) kaB[x] = read_k(bq, HALF, KH + x);
+          if constexpr (PV) read_v(vaB[x], bp, HALF, 1, x);
+          if constexpr (PV) mfma_pv(vaA[x], 0, x);
+          if constexpr (QK) mfma_qk(kaA[x], x);
+          if constexpr (SM) {
+#pragma unroll
+            for (int cc = 0; cc < CPS; ++cc) softmax_chunk(x * CPS + cc);
+          }
+          if constexpr (QK && HALF == 1) {
+            // id of the block whose K is copied after the barrier below, through the scalar cache
+            if (x == SLOTS - 1) jk = kv[(Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1];
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (QK && HALF == 1) {
+          // One barrier per KV block.  Before it, this wave's copies have landed and its reads of
+          // block Tq's K and block Tq-1's V are complete; after it, everybody's: K of block Tq+1 and
+          // V of block Tq may be read, and the two retired buffers are refilled.
+          if constexpr (SM) {   // the first half of the softmax stays on this side (see the pin further down)
+#pragma unroll
+            for (int qt = 0; qt < C::QT; ++qt) asm volatile("" ::"v"(Pb[1 - PAR][0][qt]), "v"(ls0[qt]), "v"(ls1[qt]));
+          }
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();
+          if (Tq + 2 < n_tiles) copy_k_tile(jk, bq);
+          if (Tq + 1 < n_tiles) copy_v_tile(j_v, 1 - bq);
+          j_v = jk;
+        }
+        // ---- second half: MFMAs on the operands read in the first half; reads for the next step
+#pragma unroll
+        for (int x = 0; x < SLOTS; ++x) {
+          if constexpr (NQK) kaA[x] = read_k(nbq, NHALF, x);
+          if constexpr (NPV) read_v(vaA[x], nbp, NHALF, 0, x);
+          if constexpr (PV) mfma_pv(vaB[x], 1, x);
+          if constexpr (QK) mfma_qk(kaB[x], KH + x);
+          if constexpr (SM) {
+#pragma unroll
+            for (int cc = 0; cc < CPS; ++cc) softmax_chunk(4 + x * CPS + cc);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
 
         // ---- slow path: raise the running max, redo the probabilities, rescale the accumulator
         //      (after V^T P^T of unit i-2, before that of unit i-1) ------------------------------
         if constexpr (SM) {
-          // pin the speculative results here: otherwise the compiler sinks the exponentials below
-          // the (rarely taken) branch, out of the block whose MFMAs they are meant to overlap with
+          // pin the speculative results here: otherwise the compiler sinks the conversions below
+          // the (rarely taken) branch, out of the slots whose MFMAs they are meant to overlap with
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt) {
             asm volatile("" ::"v"(Pb[1 - PAR][0][qt]), "v"(Pb[1 - PAR][1][qt]), "v"(l_spec[qt]));
@@ -450,7 +491,8 @@ void dbsp_fwd_kernel(
               const float m_new = fmaxf(m_run[qt], max_xor32(lane_max(qt)));
               const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * c);
               m_run[qt] = m_new;
-              l_spec[qt] = l_run[qt] * alpha + probabilities(qt, m_new * c);
+              mc_run[qt] = m_new * c;
+              l_spec[qt] = l_run[qt] * alpha + probabilities(qt, mc_run[qt]);
 #pragma unroll
               for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -466,26 +508,32 @@ void dbsp_fwd_kernel(
       using T1 = std::integral_constant<int, 1>;
       using Yes = std::true_type;
       using No = std::false_type;
-      // fill (two steps), steady state, drain (two steps); NU is even, so parities are static
       using B0 = std::integral_constant<int, 0>;
       using B1 = std::integral_constant<int, 1>;
       using Bx = std::integral_constant<int, -1>;
-      step(0, T0{}, Yes{}, No{}, No{}, B0{});
-      step(1, T1{}, Yes{}, Yes{}, No{}, B0{});
+      // K of block 0 is there for everybody: read the first operands of step 0
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < KH; ++x) kaA[x] = read_k(0, 0, x);
+      // fill (two steps), steady state, drain (two steps); NU is even, so parities are static.  A
+      // step may read K operands for a K Q^T stage that does not follow (last block): they are
+      // stale LDS contents and go unused.
+      step(0, T0{}, Yes{}, No{}, No{}, B0{}, Yes{}, No{});
+      step(1, T1{}, Yes{}, Yes{}, No{}, B0{}, Yes{}, Yes{});
       int i = 2;
       for (; i + 2 < NU; i += 4) {           // two KV blocks per trip: odd block, then even block
-        step(i, T0{}, Yes{}, Yes{}, Yes{}, B1{});
-        step(i + 1, T1{}, Yes{}, Yes{}, Yes{}, B1{});
-        step(i + 2, T0{}, Yes{}, Yes{}, Yes{}, B0{});
-        step(i + 3, T1{}, Yes{}, Yes{}, Yes{}, B0{});
+        step(i, T0{}, Yes{}, Yes{}, Yes{}, B1{}, Yes{}, Yes{});
+        step(i + 1, T1{}, Yes{}, Yes{}, Yes{}, B1{}, Yes{}, Yes{});
+        step(i + 2, T0{}, Yes{}, Yes{}, Yes{}, B0{}, Yes{}, Yes{});
+        step(i + 3, T1{}, Yes{}, Yes{}, Yes{}, B0{}, Yes{}, Yes{});
       }
       if (i < NU) {                          // one odd block left
-        step(i, T0{}, Yes{}, Yes{}, Yes{}, B1{});
-        step(i + 1, T1{}, Yes{}, Yes{}, Yes{}, B1{});
+        step(i, T0{}, Yes{}, Yes{}, Yes{}, B1{}, Yes{}, Yes{});
+        step(i + 1, T1{}, Yes{}, Yes{}, Yes{}, B1{}, Yes{}, Yes{});
       }
-      step(NU, T0{}, No{}, Yes{}, Yes{}, Bx{});
-      step(NU + 1, T1{}, No{}, No{}, Yes{}, Bx{});
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant last K copy must not outlive the item
+      step(NU, T0{}, No{}, Yes{}, Yes{}, Bx{}, No{}, Yes{});
+      step(NU + 1, T1{}, No{}, No{}, Yes{}, Bx{}, No{}, No{});
 
       // ---- end of item: combine the key halves (if the block has two) and store ----------------
       __syncthreads();   // every wave is done reading the K/V tiles: the buffers become the exchange area
