@@ -74,6 +74,9 @@ typedef struct dbsp_plan_opts {
                              accumulated time, sum of weight * cost[g], instead of accumulated weight (list
                              scheduling on compute units of different speed); equal costs or NULL give the
                              paper's rule.  Read during the call only.  rho_s stays on pure block counts */
+  int32_t max_batch;      /* >= 0; the largest B sparse_attn_fwd will be called with on this plan (0 -> 1).  Rows
+                             that are split need device scratch per batch entry; it is allocated here, at plan
+                             time, so that the forward call never allocates or waits */
 } dbsp_plan_opts;
 
 /*
@@ -89,14 +92,17 @@ typedef struct dbsp_plan_opts {
  * KV-block index list per row; work items (head, q_block, kv_begin, kv_end) in row-major order
  * with long rows split; greedy placement: stable sort by weight descending, each item to the
  * partition with the smallest accumulated weight (ties: lowest index); each partition's list
- * in ascending item order (round order for DBSP_MODE_ROUNDS); rho_s of the naive, the greedy and
- * the chosen placement (Eq. 1 with one period).
+ * in ascending item order (round order for DBSP_MODE_ROUNDS); rho_s of the chosen placement (Eq. 1
+ * with one period; that of the naive and of the greedy placement on request, see dbsp_plan_stats).
  * Unless DBSP_PLAN_HOST_ONLY is set, the arrays are then copied to the current device, next to
- * scratch for split rows and busy-time capture.  The copy is asynchronous (a stream of the
- * library's own, pinned staging, buffers recycled from a process-wide pool): the call returns
- * without waiting for it, and sparse_attn_fwd makes its stream wait for the copy, so planning the
- * next call overlaps with the device's work on the current one.  Masks over 1 MB are counted and
- * compacted on up to 8 host threads (joined before the call returns).
+ * scratch for split rows (max_batch batch entries) and busy-time capture.  The copy is
+ * asynchronous (a stream of the library's own, pinned staging, buffers recycled from a
+ * process-wide pool): the call returns without waiting for it, and sparse_attn_fwd makes its
+ * stream wait for the copy, so planning the next call overlaps with the device's work on the
+ * current one.  Masks over 1 MB are counted on up to 8 host threads; the index lists are written
+ * straight into pinned memory by helper threads while the calling thread builds items and
+ * placement (the helpers belong to a process-wide pool and sleep between plans; all of them are
+ * done before the call returns).
  * Errors: DBSP_EINVAL, DBSP_ENOMEM, DBSP_EHIP.  Rows with no active block are legal.
  */
 int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
@@ -124,7 +130,11 @@ int plan_sparse_attn_reuse(const dbsp_plan* previous, const uint8_t* mask_host, 
                            double* rho_under_previous);
 
 /*
- * sparse_attn_fwd -- block-sparse attention forward over a plan's work list.
+ * sparse_attn_fwd -- block-sparse attention forward over a plan's work list: per head,
+ * O = softmax(Q K^T / sqrt(d)) V (paper: Background, "Visual Generative Models") with the
+ * scores of every (query block, key block) pair outside the mask left out, i.e. computed on the
+ * dense blocks only (paper: Background, "Block-wise Sparse Attention": the dense-block count is
+ * the workload), in the order and on the compute units the plan's work list fixes.
  *
  * q:   device, bf16 [B, H, Nq, d] contiguous (d fastest);  k, v: device, bf16 [B, H, Nk, d].
  * o:   device, bf16 [B, H, Nq, d], written.  lse: device, f32 [B, H, Nq], written; may be NULL.
@@ -134,8 +144,8 @@ int plan_sparse_attn_reuse(const dbsp_plan* previous, const uint8_t* mask_host, 
  * softmax_scale <= 0 selects 1 / sqrt(d).  A query row with no active block gets O = 0, LSE = -inf.
  * stream: a hipStream_t (NULL = default stream).  The call only enqueues work: one persistent
  * kernel with one workgroup per partition, plus a small fix-up kernel when rows were split or
- * are empty.  It does not synchronise with the host.  bf16 inputs, f32 accumulation.
- * Errors: DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM (scratch growth for B > 1), DBSP_EHIP.
+ * are empty.  It neither allocates nor synchronises with the host.  bf16 inputs, f32 accumulation.
+ * Errors: DBSP_EINVAL (also: B above the plan's max_batch when rows are split), DBSP_ESHAPE, DBSP_EHIP.
  */
 int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
                     float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
@@ -147,17 +157,6 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
  * work gives 1.0.  Errors: DBSP_EINVAL (null pointer, non-positive size, negative entry).
  */
 int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, double* rho_out);
-
-/*
- * dbsp_mfma_probe -- the chip's sustained dense bf16 MFMA rate, measured on the spot (diagnostic: the
- * roofline's published peak assumes 2.4 GHz, the sustained rate shows what clock the chip holds).
- * Runs a kernel of back-to-back v_mfma_f32_32x32x16_bf16 on pseudo-random operands (eight waves per
- * compute unit; the rate a chip sustains depends on how many bits flip) four times, about 10 ms each,
- * on `stream`, synchronises and reports the last run.  tflops (required): achieved TFLOP/s; clock_ghz (may be
- * NULL): shader clock during the run.  Allocates and frees a small device buffer.
- * Errors: DBSP_EINVAL, DBSP_EHIP.
- */
-int dbsp_mfma_probe(double* tflops, double* clock_ghz, void* stream);
 
 /*
  * dbsp_fit_cost_model -- least-squares fit of  time = a * blocks + c * items + t0  over n
@@ -252,8 +251,10 @@ int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_
 /* dbsp_plan_stats: any output pointer may be NULL.  rho_* are Eq. 1 (one period) on pure block
  * counts of the SAME item list under three placements: naive, greedy longest-first (balanced),
  * and the one this plan uses (rho_plan; equals one of the other two unless the mode is
- * DBSP_MODE_ROUNDS).  plan_usec is the host time spent inside plan_sparse_attn (including the
- * device upload). */
+ * DBSP_MODE_ROUNDS or the placement was carried over).  rho_naive / rho_balanced of a placement
+ * the plan does not use are worked out on the first call that asks for them (one placement pass
+ * each, on the calling thread; ask with NULL to skip it).  plan_usec is the host time spent inside
+ * plan_sparse_attn (including handing the upload to the device).  Errors: DBSP_EINVAL, DBSP_ENOMEM. */
 int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanced, double* rho_plan,
                     int64_t* nnz, int64_t* n_items, int32_t* num_partitions, int32_t* max_item_len,
                     double* plan_usec);

@@ -5,6 +5,11 @@ include/dbsp.h; this package is its thin Python binding.
 """
 
 from .binding import (  # noqa: F401
+    DBSP_EHIP,
+    DBSP_EINVAL,
+    DBSP_ENOMEM,
+    DBSP_ESHAPE,
+    DBSP_OK,
     DbspError,
     MODE_BALANCED,
     MODE_NAIVE,

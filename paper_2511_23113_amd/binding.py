@@ -37,7 +37,7 @@ class DbspError(RuntimeError):
 class PlanOpts(C.Structure):
     _fields_ = [("num_partitions", C.c_int32), ("mode", C.c_int32), ("max_item_len", C.c_int32),
                 ("item_overhead", C.c_int32), ("flags", C.c_int32), ("locality_groups", C.c_int32),
-                ("partition_cost", C.c_void_p)]
+                ("partition_cost", C.c_void_p), ("max_batch", C.c_int32)]
 
 
 _lib = None
@@ -119,18 +119,22 @@ class Plan:
         buf = C.cast(data, C.POINTER(ctype * count.value)).contents
         return np.frombuffer(buf, dtype=dt).copy()
 
-    def stats(self) -> dict:
+    def stats(self, with_rho: bool = True) -> dict:
+        """dbsp_plan_stats.  with_rho=False leaves out rho_naive / rho_balanced (the library works those
+        out on request: each costs a placement pass unless it is the placement the plan uses)."""
         rn, rb, rp, pu = C.c_double(), C.c_double(), C.c_double(), C.c_double()
         nnz, ni = C.c_int64(), C.c_int64()
         P, L = C.c_int32(), C.c_int32()
-        _check(load_library().dbsp_plan_stats(self.handle, C.byref(rn), C.byref(rb), C.byref(rp), C.byref(nnz), C.byref(ni),
-                                              C.byref(P), C.byref(L), C.byref(pu)))
-        return dict(rho_naive=rn.value, rho_balanced=rb.value, rho_plan=rp.value, nnz=nnz.value, n_items=ni.value,
-                    num_partitions=P.value, max_item_len=L.value, plan_usec=pu.value)
+        _check(load_library().dbsp_plan_stats(self.handle, C.byref(rn) if with_rho else None, C.byref(rb) if with_rho else None,
+                                              C.byref(rp), C.byref(nnz), C.byref(ni), C.byref(P), C.byref(L), C.byref(pu)))
+        out = dict(rho_plan=rp.value, nnz=nnz.value, n_items=ni.value, num_partitions=P.value, max_item_len=L.value, plan_usec=pu.value)
+        if with_rho:
+            out.update(rho_naive=rn.value, rho_balanced=rb.value)
+        return out
 
     def busy(self, stream=None):
         """(busy ticks uint64 [P] at 100 MHz, hw ids uint32 [P]) of the last forward call; synchronises."""
-        P = self.stats()["num_partitions"]
+        P = self.stats(with_rho=False)["num_partitions"]
         ticks = np.zeros(P, dtype=np.uint64)
         hw = np.zeros(P, dtype=np.uint32)
         _check(load_library().dbsp_plan_busy(self.handle, ticks.ctypes.data_as(C.c_void_p),
@@ -140,7 +144,7 @@ class Plan:
     def calibrate(self, stream=None):
         """Relative time per block of every partition in the last forward call (int32 [P], mean about 1024):
         pass it as partition_cost to later plans with the same partition count.  Synchronises."""
-        cost = np.zeros(self.stats()["num_partitions"], dtype=np.int32)
+        cost = np.zeros(self.stats(with_rho=False)["num_partitions"], dtype=np.int32)
         _check(load_library().dbsp_plan_calibrate(self.handle, cost.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
         return cost
 
@@ -158,7 +162,7 @@ class Plan:
 
 def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
                      max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False,
-                     locality_groups: int = 0, partition_cost=None) -> Plan:
+                     locality_groups: int = 0, partition_cost=None, max_batch: int = 0) -> Plan:
     """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.ndim != 3:
@@ -171,7 +175,7 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
     opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
-                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None)
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch)
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
     return Plan(out.value, H, nQ, nK, block)
@@ -179,7 +183,7 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
 
 def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,
                            max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False, locality_groups: int = 0,
-                           partition_cost=None):
+                           partition_cost=None, max_batch: int = 0):
     """Plan the next mask of a sequence, keeping `previous`'s placement while rho_s under it stays
     <= reuse_threshold (see dbsp.h: plan_sparse_attn_reuse).  Returns (Plan, reused, rho_under_previous)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
@@ -192,7 +196,7 @@ def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_par
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
     opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
-                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None)
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch)
     out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
     _check(load_library().plan_sparse_attn_reuse(previous.handle, mask.ctypes.data_as(C.c_void_p), C.byref(opts),
                                                  float(reuse_threshold), C.byref(out), C.byref(reused), C.byref(rho)))

@@ -112,51 +112,43 @@ void free_device(dbsp_device_plan& d) {
   if (d.uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.uploaded));
   pool_put(g_dev_pool, false, d.device, d.blob, d.blob_bytes);
   pool_put(g_pin_pool, true, d.device, d.staging, d.staging_bytes);
-  if (d.big_scratch) (void)hipFree(d.big_scratch);
+  pool_put(g_pin_pool, true, d.device, d.staging_kv, d.staging_kv_bytes);
   (void)hipGetLastError();
   d = dbsp_device_plan();
 }
 
-// Makes sure the split-row scratch holds `batches` batch entries at head dim `d`.
-int ensure_scratch(const dbsp_plan* plan, int32_t batches, int32_t d) {
+// Pinned memory for the index lists (nnz + 8 int32): the compaction writes straight into it, it is
+// the source of the upload and the plan's host copy of the lists.
+int get_kv_staging(dbsp_plan* plan) {
   dbsp_device_plan& dv = plan->dev;
-  const dbsp_host_plan& hp = plan->host;
-  if (hp.n_slots == 0) return DBSP_OK;
-  const int64_t rows = (int64_t)batches * hp.n_slots * hp.block;
-  if (rows * d <= dv.scratch_floats && rows <= dv.scratch_rows) return DBSP_OK;
-  // rare: batch > 1.  The old scratch may still be in use by an earlier launch on this plan.
-  if (dv.used) (void)hipEventSynchronize(static_cast<hipEvent_t>(dv.last_use));
-  if (dv.big_scratch) { (void)hipFree(dv.big_scratch); dv.big_scratch = nullptr; }
-  hipError_t e = hipMalloc(&dv.big_scratch, (size_t)(rows * d + rows) * sizeof(float));
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    dv.scratch_floats = dv.scratch_rows = 0;
-    return fail(DBSP_ENOMEM, std::string("split-row scratch: ") + hipGetErrorString(e));
-  }
-  dv.part_o = dv.big_scratch;
-  dv.part_lse = dv.big_scratch + rows * d;
-  dv.scratch_floats = rows * d;
-  dv.scratch_rows = rows;
+  DBSP_HIP(hipGetDevice(&dv.device));
+  const size_t bytes = ((size_t)plan->host.nnz + 8) * sizeof(int32_t);
+  hipError_t e = pool_get(g_pin_pool, true, dv.device, bytes, &dv.staging_kv, &dv.staging_kv_bytes);
+  if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan staging buffer: ") + hipGetErrorString(e)); }
   return DBSP_OK;
 }
 
-// Copies the plan to the device: one pinned staging buffer, one asynchronous copy on the
-// library's upload stream, one event that forward launches wait for.  The host does not wait.
+// Copies the plan to the device: the index lists from their pinned buffer, the small arrays through
+// a second pinned staging buffer, both asynchronously on the library's upload stream, and one event
+// that forward launches wait for.  The host does not wait.
 int upload(dbsp_plan* plan) {
   dbsp_host_plan& hp = plan->host;
   dbsp_device_plan& dv = plan->dev;
-  DBSP_HIP(hipGetDevice(&dv.device));
-  const std::vector<int32_t>* arrays[] = {&hp.row_ptr,    &hp.kv_idx,     &hp.items,    &hp.item_slot,
-                                          &hp.split_rows, &hp.empty_rows, &hp.part_ptr, &hp.part_items};
-  size_t off[9];   // in int32 units, each array 16-byte aligned
+  const std::vector<int32_t>* arrays[] = {&hp.row_ptr,    &hp.items,      &hp.item_slot, &hp.split_rows,
+                                          &hp.empty_rows, &hp.part_ptr,   &hp.part_items};
+  constexpr int NA = 7;
+  size_t off[NA + 1];   // in int32 units, each array 16-byte aligned
   off[0] = 0;
-  for (int i = 0; i < 8; ++i) off[i + 1] = off[i] + ((arrays[i]->size() + 3) & ~size_t(3));
-  const size_t ints_bytes = off[8] * sizeof(int32_t);
+  for (int i = 0; i < NA; ++i) off[i + 1] = off[i] + ((arrays[i]->size() + 3) & ~size_t(3));
+  const size_t ints_bytes = off[NA] * sizeof(int32_t);
   const size_t busy_off = (ints_bytes + 255) & ~size_t(255);
   const size_t hw_off = busy_off + (((size_t)hp.P * sizeof(uint64_t) + 255) & ~size_t(255));
-  const size_t up_bytes = hw_off + (((size_t)hp.P * sizeof(uint32_t) + 255) & ~size_t(255));   // uploaded part ends here
-  const int64_t rows = (int64_t)hp.n_slots * hp.block;    // scratch for one batch entry at d = 128
-  const size_t lse_off = up_bytes;
+  const size_t up_bytes = hw_off + (((size_t)hp.P * sizeof(uint32_t) + 255) & ~size_t(255));   // staged part ends here
+  const size_t kv_off = up_bytes;
+  const size_t kv_bytes = (size_t)hp.nnz * sizeof(int32_t);
+  // split-row scratch for max_batch batch entries at d = 128
+  const int64_t rows = (int64_t)dv.max_batch * hp.n_slots * hp.block;
+  const size_t lse_off = (kv_off + kv_bytes + 255) & ~size_t(255);
   const size_t po_off = lse_off + (((size_t)rows * sizeof(float) + 255) & ~size_t(255));
   const size_t total = po_off + (size_t)rows * 128 * sizeof(float);
 
@@ -168,7 +160,7 @@ int upload(dbsp_plan* plan) {
   if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan staging buffer: ") + hipGetErrorString(e)); }
 
   unsigned char* st = static_cast<unsigned char*>(dv.staging);
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < NA; ++i)
     if (!arrays[i]->empty()) std::memcpy(st + off[i] * sizeof(int32_t), arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
   std::memset(st + busy_off, 0, up_bytes - busy_off);   // busy ticks and hardware ids start at zero
 
@@ -180,23 +172,22 @@ int upload(dbsp_plan* plan) {
   hipStream_t us;
   DBSP_HIP(upload_stream(dv.device, &us));
   DBSP_HIP(hipMemcpyAsync(dv.blob, st, up_bytes, hipMemcpyHostToDevice, us));
+  if (kv_bytes) DBSP_HIP(hipMemcpyAsync(dv.blob + kv_off, dv.staging_kv, kv_bytes, hipMemcpyHostToDevice, us));
   DBSP_HIP(hipEventRecord(ev_up, us));
 
   const int32_t* ints = reinterpret_cast<const int32_t*>(dv.blob);
   dv.row_ptr = ints + off[0];
-  dv.kv_idx = ints + off[1];
-  dv.items = ints + off[2];
-  dv.item_slot = ints + off[3];
-  dv.split_rows = ints + off[4];
-  dv.empty_rows = ints + off[5];
-  dv.part_ptr = ints + off[6];
-  dv.part_items = ints + off[7];
+  dv.items = ints + off[1];
+  dv.item_slot = ints + off[2];
+  dv.split_rows = ints + off[3];
+  dv.empty_rows = ints + off[4];
+  dv.part_ptr = ints + off[5];
+  dv.part_items = ints + off[6];
+  dv.kv_idx = reinterpret_cast<const int32_t*>(dv.blob + kv_off);
   dv.busy = reinterpret_cast<uint64_t*>(dv.blob + busy_off);
   dv.hw_id = reinterpret_cast<uint32_t*>(dv.blob + hw_off);
   dv.part_lse = reinterpret_cast<float*>(dv.blob + lse_off);
   dv.part_o = reinterpret_cast<float*>(dv.blob + po_off);
-  dv.scratch_rows = rows;
-  dv.scratch_floats = rows * 128;
   dv.resident = true;
   return DBSP_OK;
 }
@@ -219,8 +210,8 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
   if (o.num_partitions < 0 || o.item_overhead < 0 || (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS) ||
-      (o.flags & ~DBSP_PLAN_HOST_ONLY) || o.locality_groups < 0)
-    return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, groups < 0, unknown mode or flag)");
+      (o.flags & ~DBSP_PLAN_HOST_ONLY) || o.locality_groups < 0 || o.max_batch < 0)
+    return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, groups < 0, max_batch < 0, unknown mode or flag)");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
   int32_t P = o.num_partitions;
   if (P == 0 && previous) P = previous->host.P;
@@ -247,13 +238,41 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   dbsp_plan* plan = new (std::nothrow) dbsp_plan();
   if (!plan) return fail(DBSP_ENOMEM, std::string(who) + ": out of host memory");
   std::string err;
-  int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups, o.partition_cost,
-                                previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
-  if (rc != DBSP_OK) {
-    delete plan;
-    return fail(rc, std::string(who) + ": " + err);
-  }
-  if (!host_only) {
+  if (host_only) {
+    int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups, o.partition_cost,
+                                  previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
+    if (rc != DBSP_OK) {
+      delete plan;
+      return fail(rc, std::string(who) + ": " + err);
+    }
+  } else {
+    // counts first; then the index lists are compacted into pinned memory on helper threads while
+    // this thread builds the items and the placement; then everything is sent to the device
+    dbsp_host_plan& hp = plan->host;
+    plan->dev.max_batch = o.max_batch > 0 ? o.max_batch : 1;
+    int rc = dbsp_plan_count(mask_host, H, nQ, nK, block, hp, err);
+    if (rc != DBSP_OK) {
+      delete plan;
+      return fail(rc, std::string(who) + ": " + err);
+    }
+    rc = get_kv_staging(plan);
+    if (rc != DBSP_OK) {
+      free_device(plan->dev);
+      delete plan;
+      return rc;
+    }
+    hp.kv_idx = static_cast<const int32_t*>(plan->dev.staging_kv);
+    dbsp_compaction job;
+    dbsp_compact_begin(mask_host, hp, static_cast<int32_t*>(plan->dev.staging_kv), job);
+    rc = dbsp_plan_place(P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups, o.partition_cost,
+                         previous ? &previous->host : nullptr, reuse_threshold, hp, err);
+    const bool compacted = dbsp_compact_end(job);
+    if (rc == DBSP_OK && !compacted) { rc = DBSP_ENOMEM; err = "out of host memory while planning"; }
+    if (rc != DBSP_OK) {
+      free_device(plan->dev);
+      delete plan;
+      return fail(rc, std::string(who) + ": " + err);
+    }
     rc = upload(plan);
     if (rc != DBSP_OK) {
       free_device(plan->dev);
@@ -314,8 +333,8 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
   int cur = -1;
   DBSP_HIP(hipGetDevice(&cur));
   if (cur != plan->dev.device) return fail(DBSP_EINVAL, "sparse_attn_fwd: the plan lives on another device than the current one");
-  int rc = ensure_scratch(plan, B, d);
-  if (rc != DBSP_OK) return rc;
+  if (B > plan->dev.max_batch && hp.n_slots > 0)
+    return fail(DBSP_EINVAL, "sparse_attn_fwd: B exceeds the max_batch the plan's split-row scratch was sized for");
 
   const dbsp_device_plan& dv = plan->dev;
   dbsp_fwd_params p;
@@ -366,7 +385,7 @@ int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_
 #define DBSP_ARR(vec) do { *data = (vec).data(); *count = (int64_t)(vec).size(); return DBSP_OK; } while (0)
   switch (what) {
     case DBSP_ROW_PTR: DBSP_ARR(hp.row_ptr);
-    case DBSP_KV_IDX: DBSP_ARR(hp.kv_idx);
+    case DBSP_KV_IDX: *data = hp.kv_idx; *count = hp.nnz; return DBSP_OK;
     case DBSP_ITEMS: DBSP_ARR(hp.items);
     case DBSP_ITEM_SLOT: DBSP_ARR(hp.item_slot);
     case DBSP_SPLIT_ROWS: DBSP_ARR(hp.split_rows);
@@ -386,8 +405,21 @@ int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanc
                     double* plan_usec) {
   if (!plan) return fail(DBSP_EINVAL, "dbsp_plan_stats: null plan");
   const dbsp_host_plan& hp = plan->host;
-  if (rho_naive) *rho_naive = hp.rho_naive;
-  if (rho_balanced) *rho_balanced = hp.rho_balanced;
+  if (rho_naive || rho_balanced) {
+    std::lock_guard<std::mutex> lk(plan->lazy_mu);
+    const bool need_n = rho_naive && !hp.have_rho_naive, need_b = rho_balanced && !hp.have_rho_balanced;
+    if (need_n || need_b) {
+      try {
+        dbsp_host_plan_lazy_rhos(hp, need_n, need_b, &hp.rho_naive, &hp.rho_balanced);
+      } catch (const std::bad_alloc&) {
+        return fail(DBSP_ENOMEM, "dbsp_plan_stats: out of host memory");
+      }
+      hp.have_rho_naive = hp.have_rho_naive || need_n;
+      hp.have_rho_balanced = hp.have_rho_balanced || need_b;
+    }
+    if (rho_naive) *rho_naive = hp.rho_naive;
+    if (rho_balanced) *rho_balanced = hp.rho_balanced;
+  }
   if (rho_plan) *rho_plan = hp.rho_mode;
   if (nnz) *nnz = hp.nnz;
   if (n_items) *n_items = hp.n_items();

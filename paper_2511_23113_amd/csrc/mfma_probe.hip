@@ -7,6 +7,7 @@
 #include <string>
 
 #include "dbsp.h"
+#include "dbsp_diag.h"
 #include "plan.hpp"
 
 namespace {

@@ -8,9 +8,14 @@
 
 #include <emmintrin.h>   // SSE2: baseline of every x86-64 host
 
+#include <unistd.h>
+
 #include <algorithm>
-#include <cstring>
 #include <atomic>
+#include <condition_variable>
+#include <cstring>
+#include <functional>
+#include <mutex>
 #include <new>
 #include <system_error>
 #include <thread>
@@ -109,7 +114,197 @@ struct LoadHeap {
   }
 };
 
+
+// Persistent helper threads for the two row passes (starting and joining threads per plan costs
+// more than the passes themselves on a 2-3 MB mask).  The pool is created on first use, lives
+// until the process ends (its threads sleep on a condition variable in between) and is used by
+// one planner at a time: a planner that finds it busy simply runs its passes on its own thread.
+// A forked child starts a pool of its own.
+class RowPool {
+ public:
+  static constexpr int kMaxThreads = 8;
+  // Runs body(k) for k in [0, n): k = 0 on the calling thread, the rest on helpers (or on the
+  // calling thread too, for helpers that could not be started).  Returns false if a body threw.
+  bool run(int n, const std::function<void(int)>& body) {
+    std::unique_lock<std::mutex> user(user_mu_, std::try_to_lock);
+    if (!user.owns_lock() || n <= 1) return run_inline(n, body);
+    ensure_workers(n - 1);
+    const int helpers = std::min<int>(n - 1, (int)workers_);
+    {
+      std::lock_guard<std::mutex> lk(mu_);
+      body_ = &body;
+      job_base_ = 1;
+      n_jobs_ = helpers;
+      pending_ = helpers;
+      failed_ = false;
+      ++generation_;
+    }
+    cv_work_.notify_all();
+    bool ok = true;
+    try {
+      body(0);
+      for (int k = helpers + 1; k < n; ++k) body(k);
+    } catch (...) { ok = false; }
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_done_.wait(lk, [&] { return pending_ == 0; });
+    body_ = nullptr;
+    return ok && !failed_;
+  }
+  // Asynchronous form: begin() hands jobs [0, n) to helper threads and returns at once; finish()
+  // runs whatever no helper took on the calling thread, waits for the helpers and reports
+  // whether every job ran without throwing.  Every begin() needs its finish(), from the same
+  // thread, with the same Async record (the caller's: several planners may be at it at once, and
+  // only the one that found the pool free gets helpers).
+  struct Async {
+    const std::function<void(int)>* body = nullptr;
+    int n = 0, started = 0;
+    bool locked = false;
+  };
+  void begin(int n, const std::function<void(int)>& body, Async& a) {
+    a.n = n;
+    a.body = &body;
+    a.started = 0;
+    a.locked = n > 0 && user_mu_.try_lock();
+    if (!a.locked) return;
+    ensure_workers(n);
+    const int helpers = std::min<int>(n, (int)workers_);
+    {
+      std::lock_guard<std::mutex> lk(mu_);
+      body_ = &body;
+      job_base_ = 0;
+      n_jobs_ = helpers;
+      pending_ = helpers;
+      failed_ = false;
+      ++generation_;
+    }
+    a.started = helpers;
+    if (helpers) cv_work_.notify_all();
+  }
+  bool finish(Async& a) {
+    bool ok = true;
+    try {
+      for (int k = a.started; k < a.n; ++k) (*a.body)(k);
+    } catch (...) { ok = false; }
+    if (a.locked) {
+      {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_done_.wait(lk, [&] { return pending_ == 0; });
+        body_ = nullptr;
+        ok = ok && !failed_;
+      }
+      user_mu_.unlock();
+      a.locked = false;
+    }
+    a.n = a.started = 0;
+    return ok;
+  }
+  static RowPool& instance() {
+    static std::mutex make_mu;
+    static RowPool* pool = nullptr;
+    static pid_t owner = 0;
+    std::lock_guard<std::mutex> lk(make_mu);
+    if (!pool || owner != getpid()) {   // first use, or first use in a forked child (the parent's threads are not there)
+      pool = new RowPool();
+      owner = getpid();
+    }
+    return *pool;
+  }
+
+ private:
+  static bool run_inline(int n, const std::function<void(int)>& body) {
+    try {
+      for (int k = 0; k < n; ++k) body(k);
+    } catch (...) { return false; }
+    return true;
+  }
+  void ensure_workers(int want) {
+    want = std::min(want, kMaxThreads);
+    while ((int)workers_ < want) {
+      try {
+        std::thread(&RowPool::worker, this, (int)workers_).detach();
+      } catch (const std::system_error&) {
+        return;   // no more threads to be had: the caller takes the remaining ranges
+      }
+      ++workers_;
+    }
+  }
+  void worker(int id) {
+    uint64_t seen = 0;
+    std::unique_lock<std::mutex> lk(mu_);
+    for (;;) {
+      cv_work_.wait(lk, [&] { return generation_ != seen; });
+      seen = generation_;
+      if (id >= n_jobs_) continue;
+      const std::function<void(int)>* body = body_;
+      const int job = id + job_base_;
+      lk.unlock();
+      bool ok = true;
+      try { (*body)(job); } catch (...) { ok = false; }
+      lk.lock();
+      if (!ok) failed_ = true;
+      if (--pending_ == 0) cv_done_.notify_all();
+    }
+  }
+  std::mutex user_mu_, mu_;
+  std::condition_variable cv_work_, cv_done_;
+  const std::function<void(int)>* body_ = nullptr;
+  uint64_t generation_ = 0;
+  int n_jobs_ = 0, pending_ = 0, job_base_ = 0;
+  size_t workers_ = 0;
+  bool failed_ = false;
+};
+
+// Stable descending order of items by weight through a counting sort: weights are bounded, and
+// filling each bucket in ascending id keeps ties stable.
+template <class Weight>
+void order_by_weight_desc(int64_t n_items, int64_t wmax, Weight weight, std::vector<int32_t>& order) {
+  std::vector<int64_t> bucket_start(wmax + 2, 0);
+  for (int64_t i = 0; i < n_items; ++i) bucket_start[wmax - weight(i) + 1]++;
+  for (int64_t w = 0; w <= wmax; ++w) bucket_start[w + 1] += bucket_start[w];
+  order.resize(n_items);
+  for (int64_t i = 0; i < n_items; ++i) order[bucket_start[wmax - weight(i)]++] = (int32_t)i;
+}
+
+std::vector<int64_t> loads_of(const dbsp_host_plan& hp, const std::vector<int32_t>& assign) {
+  std::vector<int64_t> ld(hp.P, 0);
+  const int64_t n_items = hp.n_items();
+  for (int64_t i = 0; i < n_items; ++i) ld[assign[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
+  return ld;
+}
+
+// naive placement: items in generation order, contiguous runs of ceil(n_items / P)
+std::vector<int32_t> place_naive(const dbsp_host_plan& hp) {
+  const int64_t n_items = hp.n_items();
+  std::vector<int32_t> assign(n_items);
+  const int64_t run = n_items ? (n_items + hp.P - 1) / hp.P : 1;
+  for (int64_t i = 0; i < n_items; ++i) assign[i] = (int32_t)(i / run);
+  return assign;
+}
+
+// greedy longest-first placement (Alg. 1, first loop)
+std::vector<int32_t> place_greedy(const dbsp_host_plan& hp) {
+  const int64_t n_items = hp.n_items();
+  std::vector<int32_t> assign(n_items), order;
+  const int64_t ov = hp.item_overhead;
+  auto weight = [&](int64_t i) { return (int64_t)(hp.items[4 * i + 3] - hp.items[4 * i + 2]) + ov; };
+  order_by_weight_desc(n_items, (int64_t)hp.nK + ov, weight, order);
+  LoadHeap heap(hp.P, hp.partition_cost.empty() ? nullptr : hp.partition_cost.data());
+  for (int64_t t = 0; t < n_items; ++t) assign[order[t]] = heap.place(weight(order[t]));
+  return assign;
+}
+
 }  // namespace
+
+void dbsp_host_plan_lazy_rhos(const dbsp_host_plan& hp, bool want_naive, bool want_balanced, double* rho_naive, double* rho_balanced) {
+  if (want_naive) {
+    const std::vector<int64_t> ld = loads_of(hp, place_naive(hp));
+    *rho_naive = dbsp_rho(ld.data(), 1, hp.P);
+  }
+  if (want_balanced) {
+    const std::vector<int64_t> ld = loads_of(hp, place_greedy(hp));
+    *rho_balanced = dbsp_rho(ld.data(), 1, hp.P);
+  }
+}
 
 double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions) {
   int64_t total = 0, num = 0;
@@ -126,47 +321,29 @@ double dbsp_rho(const int64_t* work, int32_t periods, int32_t partitions) {
   return (double)num / ((double)total / (double)partitions);
 }
 
-int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
-                         int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                         int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
-                         double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
+namespace {
+int row_threads(int64_t mask_bytes) {
+  if (mask_bytes < (int64_t)1 << 20) return 1;
+  const unsigned hw = std::thread::hardware_concurrency();
+  return (int)std::min<int64_t>(std::min<unsigned>(hw ? hw : 1, RowPool::kMaxThreads), mask_bytes >> 19);
+}
+}  // namespace
+
+int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block, dbsp_host_plan& hp, std::string& err) {
   try {
     const int64_t R = (int64_t)H * nQ;
     hp.H = H; hp.nQ = nQ; hp.nK = nK; hp.block = block;
-    hp.P = P; hp.mode = mode; hp.item_overhead = item_overhead;
-
-    // pass 1: per-row counts (Alg. 1's get_blocks_per_head, kept per row), row offsets.
-    // Rows are independent: large masks are cut into contiguous row ranges, one per thread.
+    // per-row counts (Alg. 1's get_blocks_per_head, kept per row), row offsets.  Rows are
+    // independent: large masks are cut into contiguous row ranges, one per thread.
     hp.row_cnt.resize(R);
     hp.row_ptr.resize(R + 1);
     hp.blocks_per_head.assign(H, 0);
-    const int64_t mask_bytes = R * nK;
-    int n_thr = 1;
-    if (mask_bytes >= (int64_t)1 << 20) {
-      const unsigned hw = std::thread::hardware_concurrency();
-      n_thr = (int)std::min<int64_t>(std::min<unsigned>(hw ? hw : 1, 8), mask_bytes >> 19);
-    }
-    std::atomic<bool> worker_failed{false};
-    auto for_row_ranges = [&](auto&& body) {   // body(first_row, last_row_exclusive)
-      if (n_thr <= 1) { body((int64_t)0, R); return; }
-      auto guarded = [&](int64_t r0, int64_t r1) {
-        try { body(r0, r1); } catch (...) { worker_failed = true; }
-      };
-      std::vector<std::thread> pool;
-      pool.reserve(n_thr - 1);
-      int started = 1;
-      try {
-        for (; started < n_thr; ++started) pool.emplace_back(guarded, R * started / n_thr, R * (started + 1) / n_thr);
-      } catch (const std::system_error&) {
-        // no more threads to be had: this thread takes the ranges that were not started
-      }
-      guarded((int64_t)0, R / n_thr);
-      if (started < n_thr) guarded(R * started / n_thr, R);
-      for (auto& th : pool) th.join();
+    const int n_thr = row_threads(R * nK);
+    const std::function<void(int)> job = [&](int k) {
+      for (int64_t r = R * k / n_thr; r < R * (k + 1) / n_thr; ++r) hp.row_cnt[r] = count_row(mask + r * nK, nK);
     };
-    for_row_ranges([&](int64_t r0, int64_t r1) {
-      for (int64_t r = r0; r < r1; ++r) hp.row_cnt[r] = count_row(mask + r * nK, nK);
-    });
+    if (n_thr <= 1) job(0);
+    else if (!RowPool::instance().run(n_thr, job)) { err = "out of host memory while planning"; return DBSP_ENOMEM; }
     hp.row_ptr[0] = 0;
     int64_t total = 0;
     for (int64_t r = 0; r < R; ++r) {
@@ -176,55 +353,109 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       hp.blocks_per_head[r / nQ] += hp.row_cnt[r];
     }
     hp.nnz = total;
-    // pass 2: ascending KV block ids of every row.  compact_row stores up to 8 elements past a
-    // row's end: harmless while that stays inside the thread's own range (later rows overwrite
-    // them) or in the slack at the very end; a row whose spill would reach the next thread's
-    // range goes through a bounce buffer.
-    hp.kv_idx.resize(total + 8);
-    for_row_ranges([&](int64_t r0, int64_t r1) {
-      int32_t* base = hp.kv_idx.data();
-      std::vector<int32_t> bounce;
-      for (int64_t r = r0; r < r1; ++r) {
-        if (!hp.row_cnt[r]) continue;
-        if (r1 == R || (int64_t)hp.row_ptr[r + 1] + 8 <= (int64_t)hp.row_ptr[r1]) {
-          compact_row(mask + r * nK, nK, base + hp.row_ptr[r]);
-        } else {
-          bounce.resize((size_t)nK + 8);
-          compact_row(mask + r * nK, nK, bounce.data());
-          std::memcpy(base + hp.row_ptr[r], bounce.data(), sizeof(int32_t) * (size_t)hp.row_cnt[r]);
-        }
+    return DBSP_OK;
+  } catch (const std::bad_alloc&) {
+    err = "out of host memory while planning";
+    return DBSP_ENOMEM;
+  }
+}
+
+// Ascending KV block ids of every row, written to dst[row_ptr[r] ...) (dst holds nnz + 8 elements).
+// compact_row stores up to 8 elements past a row's end: harmless while that stays inside the
+// thread's own range (later rows overwrite them) or in the slack at the very end; a row whose
+// spill would reach the next thread's range goes through a bounce buffer.
+void dbsp_compact_begin(const uint8_t* mask, const dbsp_host_plan& hp, int32_t* dst, dbsp_compaction& job) {
+  const int64_t R = (int64_t)hp.H * hp.nQ;
+  const int32_t nK = hp.nK;
+  const int n_thr = row_threads(R * nK);
+  const dbsp_host_plan* php = &hp;
+  job.body = [=](int k) {
+    const dbsp_host_plan& h = *php;
+    const int64_t r0 = R * k / n_thr, r1 = R * (k + 1) / n_thr;
+    std::vector<int32_t> bounce;
+    for (int64_t r = r0; r < r1; ++r) {
+      if (!h.row_cnt[r]) continue;
+      if (r1 == R || (int64_t)h.row_ptr[r + 1] + 8 <= (int64_t)h.row_ptr[r1]) {
+        compact_row(mask + r * nK, nK, dst + h.row_ptr[r]);
+      } else {
+        bounce.resize((size_t)nK + 8);
+        compact_row(mask + r * nK, nK, bounce.data());
+        std::memcpy(dst + h.row_ptr[r], bounce.data(), sizeof(int32_t) * (size_t)h.row_cnt[r]);
       }
-    });
-    hp.kv_idx.resize(total);
-    if (worker_failed) { err = "out of host memory while planning"; return DBSP_ENOMEM; }
+    }
+  };
+  if (n_thr <= 1 && R * nK < ((int64_t)1 << 18)) {   // a small mask: done before a helper thread would have woken up
+    job.pool = nullptr;
+    job.body(0);
+    return;
+  }
+  job.pool = &RowPool::instance();
+  auto* async = new RowPool::Async();
+  job.state = async;
+  static_cast<RowPool*>(job.pool)->begin(n_thr, job.body, *async);
+}
+
+bool dbsp_compact_end(dbsp_compaction& job) {
+  if (!job.pool) return true;
+  auto* async = static_cast<RowPool::Async*>(job.state);
+  const bool ok = static_cast<RowPool*>(job.pool)->finish(*async);
+  delete async;
+  job.pool = job.state = nullptr;
+  return ok;
+}
+
+int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
+                    int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
+                    double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
+  try {
+    const int32_t H = hp.H, nQ = hp.nQ, nK = hp.nK;
+    const int64_t R = (int64_t)H * nQ;
+    hp.P = P; hp.mode = mode; hp.item_overhead = item_overhead;
 
     // split threshold
     int32_t L = max_item_len;
     if (L == 0) L = (int32_t)std::max<int64_t>(4, hp.nnz / (2 * (int64_t)P));   // half the mean partition load
     hp.max_item_len = L;
 
-    // items in row-major order
-    hp.items.clear(); hp.item_slot.clear(); hp.split_rows.clear(); hp.empty_rows.clear();
-    hp.items.reserve(4 * (R + 64)); hp.item_slot.reserve(R + 64);
-    hp.n_slots = 0;
+    // items in row-major order: sizes first, then indexed writes
+    int64_t ni = 0, n_split = 0, n_empty = 0;
     for (int64_t r = 0; r < R; ++r) {
       const int32_t c = hp.row_cnt[r];
-      const int32_t h = (int32_t)(r / nQ), I = (int32_t)(r % nQ);
-      if (c == 0) { hp.empty_rows.push_back((int32_t)r); continue; }
-      if (L < 0 || c <= L) {
-        hp.items.insert(hp.items.end(), {h, I, 0, c});
-        hp.item_slot.push_back(-1);
-        continue;
-      }
-      const int32_t k = (c + L - 1) / L, base = c / k, extra = c % k;
-      hp.split_rows.insert(hp.split_rows.end(), {(int32_t)r, hp.n_slots, k, 0});
-      int32_t pos = 0;
-      for (int32_t t = 0; t < k; ++t) {
-        const int32_t len = base + (t < extra ? 1 : 0);
-        hp.items.insert(hp.items.end(), {h, I, pos, pos + len});
-        hp.item_slot.push_back(hp.n_slots++);
-        pos += len;
-      }
+      if (c == 0) ++n_empty;
+      else if (L < 0 || c <= L) ++ni;
+      else { ni += (c + L - 1) / L; ++n_split; }
+    }
+    if (ni > (int64_t)INT32_MAX / 4) { err = "too many work items"; return DBSP_EINVAL; }
+    hp.items.resize(4 * ni); hp.item_slot.resize(ni); hp.split_rows.resize(4 * n_split); hp.empty_rows.resize(n_empty);
+    hp.n_slots = 0;
+    {
+      int32_t* it = hp.items.data();
+      int32_t* sl = hp.item_slot.data();
+      int32_t* sr = hp.split_rows.data();
+      int32_t* er = hp.empty_rows.data();
+      int64_t r = 0;
+      for (int32_t h = 0; h < H; ++h)
+        for (int32_t I = 0; I < nQ; ++I, ++r) {
+          const int32_t c = hp.row_cnt[r];
+          if (c == 0) { *er++ = (int32_t)r; continue; }
+          if (L < 0 || c <= L) {
+            it[0] = h; it[1] = I; it[2] = 0; it[3] = c;
+            it += 4;
+            *sl++ = -1;
+            continue;
+          }
+          const int32_t k = (c + L - 1) / L, base = c / k, extra = c % k;
+          sr[0] = (int32_t)r; sr[1] = hp.n_slots; sr[2] = k; sr[3] = 0;
+          sr += 4;
+          int32_t pos = 0;
+          for (int32_t t = 0; t < k; ++t) {
+            const int32_t len = base + (t < extra ? 1 : 0);
+            it[0] = h; it[1] = I; it[2] = pos; it[3] = pos + len;
+            it += 4;
+            *sl++ = hp.n_slots++;
+            pos += len;
+          }
+        }
     }
     const int64_t n_items = hp.n_items();
 
@@ -264,34 +495,18 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       hp.reused = hp.rho_reuse <= reuse_threshold;
     }
 
-    // naive placement: contiguous runs of ceil(n_items / P)
-    std::vector<int32_t> assign_naive(n_items), assign_lpt(n_items);
-    const int64_t run = n_items ? (n_items + P - 1) / P : 1;
-    for (int64_t i = 0; i < n_items; ++i) assign_naive[i] = (int32_t)(i / run);
-
-    // greedy placement.  Stable descending order by weight through a counting sort: weights
-    // are bounded by nK + item_overhead, and filling each bucket in ascending id keeps ties stable.
-    {
-      const int64_t wmax = (int64_t)nK + item_overhead;
-      std::vector<int64_t> bucket_start(wmax + 2, 0);
-      auto weight = [&](int64_t i) { return (int64_t)(hp.items[4 * i + 3] - hp.items[4 * i + 2]) + item_overhead; };
-      for (int64_t i = 0; i < n_items; ++i) bucket_start[wmax - weight(i) + 1]++;
-      for (int64_t w = 0; w <= wmax; ++w) bucket_start[w + 1] += bucket_start[w];
-      std::vector<int32_t> order(n_items);
-      for (int64_t i = 0; i < n_items; ++i) order[bucket_start[wmax - weight(i)]++] = (int32_t)i;
-      LoadHeap heap(P, partition_cost);
-      for (int64_t t = 0; t < n_items; ++t) {
-        const int32_t i = order[t];
-        assign_lpt[i] = heap.place(weight(i));
-      }
-    }
+    // The placement asked for; rho_s of the other ones is worked out only when dbsp_plan_stats asks.
+    hp.partition_cost.assign(partition_cost ? partition_cost : nullptr, partition_cost ? partition_cost + P : nullptr);
+    std::vector<int32_t> assign_naive, assign_lpt;
+    if (!hp.reused && mode == DBSP_MODE_NAIVE) assign_naive = place_naive(hp);
+    if (!hp.reused && mode == DBSP_MODE_BALANCED) assign_lpt = place_greedy(hp);
 
     // round-based greedy (DBSP_MODE_ROUNDS): heads in descending order of their block count
     // (the sort of Alg. 1), their items cut into consecutive rounds of P; inside a round the
     // k-th heaviest item goes to the k-th least-loaded partition.  Every partition works on the
     // same head at about the same time, which is what lets the KV blocks be reused from L2.
     std::vector<int32_t> assign_rounds, seq;
-    if (mode == DBSP_MODE_ROUNDS) {
+    if (mode == DBSP_MODE_ROUNDS && !hp.reused) {
       auto weight = [&](int64_t i) { return (int64_t)(hp.items[4 * i + 3] - hp.items[4 * i + 2]) + item_overhead; };
       std::vector<int32_t> head_order(H);
       for (int32_t h = 0; h < H; ++h) head_order[h] = h;
@@ -309,20 +524,43 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
       // query blocks -- and the same greedy runs one level up: heaviest chunk first, each to the
       // least-loaded group that has no chunk yet in this round.
       const int32_t G = locality_groups > 1 ? locality_groups : 1, per = P / G;
+      const int64_t wmax = (int64_t)nK + item_overhead;
       std::vector<int64_t> load(P, 0), chunk_w(G), group_load(G);
-      std::vector<int32_t> parts(per), idx, chunk_order(G);
+      std::vector<int32_t> chunk_order(G);
       std::vector<char> taken(G);
+      std::vector<int32_t> wseq(n_items);            // weights in sequence order
+      for (int64_t t = 0; t < n_items; ++t) wseq[t] = (int32_t)weight(seq[t]);
+      // Both orders inside a chunk -- items by weight, descending and stable; a group's partitions
+      // by accumulated load, ascending and stable -- are orders of distinct integers
+      // (key << 20 | position) and come from plain integer sorts.  The keys hold a position in 20
+      // bits and a weight or a load above it; inputs too large for that take the comparison sorts.
+      int64_t cost_max = 1;
+      if (partition_cost) cost_max = *std::max_element(partition_cost, partition_cost + P);
+      const bool packed_keys = per < (1 << 20) && wmax < ((int64_t)1 << 40) &&
+                               (hp.nnz + (int64_t)item_overhead * n_items) < (((int64_t)1 << 43) / cost_max);
+      std::vector<uint64_t> item_key(per), part_key(per);
+      std::vector<int32_t> item_pos(per), part_rank(per);   // part_rank: positions k of a group's partitions (partition = g + k G), by load
+      auto insertion_sort = [](auto* first, int64_t n, auto less) {
+        for (int64_t a = 1; a < n; ++a) {
+          auto v = first[a];
+          int64_t b = a;
+          for (; b > 0 && less(v, first[b - 1]); --b) first[b] = first[b - 1];
+          first[b] = v;
+        }
+      };
       for (int64_t r0 = 0; r0 < n_items; r0 += P) {
         const int64_t r1 = std::min<int64_t>(n_items, r0 + P);
         for (int32_t j = 0; j < G; ++j) {
           chunk_w[j] = 0;
-          for (int64_t t = r0 + (int64_t)j * per; t < std::min<int64_t>(r1, r0 + (int64_t)(j + 1) * per); ++t) chunk_w[j] += weight(seq[t]);
+          for (int64_t t = r0 + (int64_t)j * per; t < std::min<int64_t>(r1, r0 + (int64_t)(j + 1) * per); ++t) chunk_w[j] += wseq[t];
           chunk_order[j] = j;
           taken[j] = 0;
           group_load[j] = 0;
         }
-        for (int32_t p = 0; p < P; ++p) group_load[p % G] += load[p];
-        std::stable_sort(chunk_order.begin(), chunk_order.end(), [&](int32_t a, int32_t b) { return chunk_w[a] > chunk_w[b]; });
+        for (int32_t k = 0, p = 0; k < per; ++k)
+          for (int32_t g = 0; g < G; ++g, ++p) group_load[g] += load[p];
+        // heaviest chunk first, stable (insertion sort is stable)
+        insertion_sort(chunk_order.data(), G, [&](int32_t a, int32_t b) { return chunk_w[a] > chunk_w[b]; });
         for (int32_t j : chunk_order) {
           int32_t gamma = -1;
           for (int32_t g = 0; g < G; ++g)
@@ -330,31 +568,39 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
           taken[gamma] = 1;
           const int64_t c0 = r0 + (int64_t)j * per, c1 = std::min<int64_t>(r1, c0 + per);
           if (c0 >= c1) continue;
-          idx.assign(seq.begin() + c0, seq.begin() + c1);
-          std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) { return weight(a) > weight(b); });
-          for (int32_t k = 0; k < per; ++k) parts[k] = gamma + k * G;
-          std::stable_sort(parts.begin(), parts.end(), [&](int32_t a, int32_t b) { return load[a] < load[b]; });
-          for (size_t k = 0; k < idx.size(); ++k) {
-            assign_rounds[idx[k]] = parts[k];
-            load[parts[k]] += partition_cost ? weight(idx[k]) * partition_cost[parts[k]] : weight(idx[k]);
+          // k-th heaviest item (stable) to the group's k-th least-loaded partition (stable)
+          const int64_t n_c = c1 - c0;
+          int32_t* rank = part_rank.data();
+          if (packed_keys) {
+            for (int64_t t = 0; t < n_c; ++t) item_key[t] = ((uint64_t)(wmax - wseq[c0 + t]) << 20) | (uint64_t)t;
+            std::sort(item_key.begin(), item_key.begin() + n_c);
+            for (int64_t t = 0; t < n_c; ++t) item_pos[t] = (int32_t)(item_key[t] & 0xFFFFF);
+            for (int32_t k = 0; k < per; ++k) part_key[k] = ((uint64_t)load[gamma + k * G] << 20) | (uint64_t)k;
+            std::sort(part_key.begin(), part_key.end());
+            for (int32_t k = 0; k < per; ++k) rank[k] = (int32_t)(part_key[k] & 0xFFFFF);
+          } else {
+            for (int64_t t = 0; t < n_c; ++t) item_pos[t] = (int32_t)t;
+            std::stable_sort(item_pos.begin(), item_pos.begin() + n_c, [&](int32_t a, int32_t b) { return wseq[c0 + a] > wseq[c0 + b]; });
+            for (int32_t k = 0; k < per; ++k) rank[k] = k;
+            std::stable_sort(rank, rank + per, [&](int32_t a, int32_t b) { return load[gamma + a * G] < load[gamma + b * G]; });
+          }
+          for (int64_t k = 0; k < n_c; ++k) {
+            const int32_t it = seq[c0 + item_pos[k]];
+            const int32_t pt = gamma + rank[k] * G;
+            assign_rounds[it] = pt;
+            load[pt] += partition_cost ? (int64_t)wseq[c0 + item_pos[k]] * partition_cost[pt] : (int64_t)wseq[c0 + item_pos[k]];
           }
         }
       }
     }
 
-    auto loads_of = [&](const std::vector<int32_t>& a) {
-      std::vector<int64_t> ld(P, 0);
-      for (int64_t i = 0; i < n_items; ++i) ld[a[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
-      return ld;
-    };
-    const std::vector<int64_t> ld_naive = loads_of(assign_naive), ld_lpt = loads_of(assign_lpt);
-    hp.rho_naive = dbsp_rho(ld_naive.data(), 1, P);
-    hp.rho_balanced = dbsp_rho(ld_lpt.data(), 1, P);
-
     const std::vector<int32_t>& assign = hp.reused ? assign_reuse
         : (mode == DBSP_MODE_NAIVE) ? assign_naive : (mode == DBSP_MODE_ROUNDS) ? assign_rounds : assign_lpt;
-    hp.part_load = loads_of(assign);
+    hp.part_load = loads_of(hp, assign);
     hp.rho_mode = dbsp_rho(hp.part_load.data(), 1, P);
+    hp.have_rho_naive = hp.have_rho_balanced = false;
+    if (!hp.reused && mode == DBSP_MODE_NAIVE) { hp.rho_naive = hp.rho_mode; hp.have_rho_naive = true; }
+    if (!hp.reused && mode == DBSP_MODE_BALANCED) { hp.rho_balanced = hp.rho_mode; hp.have_rho_balanced = true; }
 
     // per-partition lists: ascending item id (= ascending head, q_block, kv_begin), or, for the
     // round-based placement, the order of the rounds
@@ -373,4 +619,25 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
     err = "out of host memory while planning";
     return DBSP_ENOMEM;
   }
+}
+
+int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
+                         int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
+                         int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
+                         double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
+  int rc = dbsp_plan_count(mask, H, nQ, nK, block, hp, err);
+  if (rc != DBSP_OK) return rc;
+  try {
+    hp.kv_store.resize(hp.nnz + 8);
+  } catch (const std::bad_alloc&) {
+    err = "out of host memory while planning";
+    return DBSP_ENOMEM;
+  }
+  hp.kv_idx = hp.kv_store.data();
+  dbsp_compaction job;
+  dbsp_compact_begin(mask, hp, hp.kv_store.data(), job);     // runs beside the placement
+  rc = dbsp_plan_place(P, mode, max_item_len, item_overhead, locality_groups, partition_cost, prev, reuse_threshold, hp, err);
+  const bool ok = dbsp_compact_end(job);
+  if (rc == DBSP_OK && !ok) { err = "out of host memory while planning"; rc = DBSP_ENOMEM; }
+  return rc;
 }

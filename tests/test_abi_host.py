@@ -11,6 +11,7 @@ import pytest
 
 import synth
 from oracle import planner as op
+import paper_2511_23113_amd as dbsp
 from paper_2511_23113_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -18,9 +19,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
-    header = open(os.path.join(ROOT, "include", "dbsp.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(?:int|void|const char\s*\*)\s+([a-z_0-9]+)\s*\(", header))
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):       # the boundary and the diagnostics header
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(?:int|void|const char\s*\*)\s+([a-z_0-9]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -307,3 +310,49 @@ def test_partition_cost_bit_exact_and_errors():
     assert lib.dbsp_plan_calibrate(pl.handle, out.ctypes.data_as(C.c_void_p), None) == B.DBSP_EINVAL   # host-only plan
     assert lib.dbsp_plan_calibrate(None, out.ctypes.data_as(C.c_void_p), None) == B.DBSP_EINVAL
     pl.close()
+
+
+def test_concurrent_planners_share_the_helper_threads_and_agree():
+    # several host threads plan a mask large enough for the threaded passes at the same time: one of
+    # them gets the library's helper threads, the others run their passes themselves; every plan
+    # must be the same as one made alone.  Also: negative max_batch is refused.
+    import threading
+    rng = np.random.default_rng(77)
+    mask = (rng.random((6, 600, 512)) < 0.25).astype(np.uint8)            # 1.8 MB
+    alone = dbsp.plan_sparse_attn(mask, 128, num_partitions=256, mode=B.MODE_ROUNDS, locality_groups=8, host_only=True)
+    want = {k: alone.array(k).tolist() for k in (B.ROW_PTR, B.KV_IDX, B.ITEMS, B.PART_PTR, B.PART_ITEMS)}
+    alone.close()
+    got, errors = [], []
+
+    def work():
+        try:
+            for _ in range(3):
+                p = dbsp.plan_sparse_attn(mask, 128, num_partitions=256, mode=B.MODE_ROUNDS, locality_groups=8, host_only=True)
+                got.append({k: p.array(k).tolist() for k in want})
+                p.close()
+        except Exception as exc:        # noqa: BLE001
+            errors.append(exc)
+
+    threads = [threading.Thread(target=work) for _ in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors and len(got) == 12 and all(g == want for g in got)
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    opts = B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY, 0, None, -1)
+    assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 64, opts)[0] == B.DBSP_EINVAL
+
+
+def test_rho_of_the_unused_placements_is_worked_out_on_request():
+    # the plan computes rho_s of its own placement; that of the naive and of the greedy placement
+    # comes on the first dbsp_plan_stats call that asks, and equals the oracle's
+    mask = synth.mask_for_config(5)
+    ref = op.plan(mask, 256, mode=op.MODE_ROUNDS, locality_groups=8)
+    p = dbsp.plan_sparse_attn(mask, 128, num_partitions=256, mode=B.MODE_ROUNDS, locality_groups=8, host_only=True)
+    light = p.stats(with_rho=False)
+    assert "rho_naive" not in light and light["rho_plan"] == ref["rho_plan"]
+    full = p.stats()
+    assert full["rho_naive"] == ref["rho_naive"] and full["rho_balanced"] == ref["rho_balanced"] and full["rho_plan"] == ref["rho_plan"]
+    assert p.stats() == full                      # the second call reads the stored values
+    p.close()

@@ -30,6 +30,7 @@ def _host_f32(t):
 def _run(mask, block, qb, kb, vb, scale=0.0, want_lse=True, **plan_kw):
     import torch
     import paper_2511_23113_amd as dbsp
+    plan_kw.setdefault("max_batch", int(qb.shape[0]))      # the split-row scratch is sized when the plan is made
     plan = dbsp.plan_sparse_attn(mask, block, **plan_kw)
     q, k, v = _dev(qb), _dev(kb), _dev(vb)
     o, lse = dbsp.sparse_attn_fwd(plan, q, k, v, softmax_scale=scale, want_lse=want_lse)
@@ -373,6 +374,28 @@ def test_scores_that_keep_growing_take_the_rescale_path(block, d):
         plan.close()
 
 
+def test_batch_beyond_the_plans_max_batch_is_refused():
+    # split rows need scratch per batch entry; it is allocated with the plan, and the forward call
+    # neither grows it nor runs with too little
+    import torch
+    import paper_2511_23113_amd as dbsp
+    block, d = 64, 64
+    mask = np.ones((1, 2, 4), dtype=np.uint8)
+    qb = synth.normal_bf16((2, 1, 2 * block, d), 41)
+    kb = synth.normal_bf16((2, 1, 4 * block, d), 42)
+    vb = synth.normal_bf16((2, 1, 4 * block, d), 43)
+    plan = dbsp.plan_sparse_attn(mask, block, num_partitions=4, max_item_len=2)          # rows are split, max_batch = 1
+    with pytest.raises(dbsp.DbspError) as ei:
+        dbsp.sparse_attn_fwd(plan, _dev(qb), _dev(kb), _dev(vb))
+    assert ei.value.code == dbsp.DBSP_EINVAL and "max_batch" in str(ei.value)
+    plan.close()
+    whole = dbsp.plan_sparse_attn(mask, block, num_partitions=4, max_item_len=-1)        # no split rows: any B goes
+    o, lse = dbsp.sparse_attn_fwd(whole, _dev(qb), _dev(kb), _dev(vb))
+    torch.cuda.synchronize()
+    _check_all_rows(mask, block, qb, kb, vb, _host_f32(o), lse.cpu().numpy())
+    whole.close()
+
+
 def test_mfma_probe_reports_a_plausible_sustained_rate():
     import paper_2511_23113_amd as dbsp
     tflops, ghz = dbsp.mfma_probe()
@@ -381,8 +404,8 @@ def test_mfma_probe_reports_a_plausible_sustained_rate():
 
 
 def test_two_batch_entries_at_full_size_share_the_plan():
-    # config 5 with B = 2 (different tensors per batch entry, one mask): the split-row scratch has to
-    # grow for the second entry, and every batch entry is checked on sampled rows, split ones included
+    # config 5 with B = 2 (different tensors per batch entry, one mask, max_batch = 2): every batch
+    # entry is checked on sampled rows, split ones included
     import torch
     import paper_2511_23113_amd as dbsp
     c = synth.config_shape(5)
