@@ -152,6 +152,25 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
                     void* stream);
 
 /*
+ * sparse_attn_fwd_static -- sparse_attn_fwd for callers that cannot allocate device memory or
+ * have it allocated for them: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same results as sparse_attn_fwd; the one
+ * difference is where the partial results of split rows go: into a static device array of the
+ * library (32 MiB per GPU, there from the moment the library is loaded until the process ends)
+ * instead of the scratch the plan allocated.  It therefore works for any B whatever the plan's
+ * max_batch, as long as  B * n_split_chunks * block * (d + 1) * 4 bytes (plus alignment) fit in
+ * the 32 MiB; beyond that it returns DBSP_EINVAL and the message names both sizes.  The call makes
+ * no allocation of any kind (its first use on a device looks up the array's device address).
+ * Nothing in the array needs clearing: every slot a launch reads was written by that launch.
+ * All calls on one GPU share the array: two such calls must not overlap on the device (different
+ * streams without ordering, or concurrent host threads), or they race on it.
+ * Errors: as sparse_attn_fwd.
+ */
+int sparse_attn_fwd_static(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
+                           float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
+                           void* stream);
+
+/*
  * imbalance_ratio -- Eq. 1 on a host matrix work[periods][partitions] (row-major, int64, >= 0):
  * rho = sum_i max_g work[i][g] / (sum_{i,g} work[i][g] / partitions), in double.  Zero total
  * work gives 1.0.  Errors: DBSP_EINVAL (null pointer, non-positive size, negative entry).

@@ -22,7 +22,7 @@ ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, 
 _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 
 EXPORTS = (
-    "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
+    "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "sparse_attn_fwd_static", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
     "dbsp_plan_busy", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
     "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model", "dbsp_mfma_probe",
 )
@@ -73,6 +73,8 @@ def load_library(path: str | None = None):
     lib.dbsp_plan_calibrate.restype = C.c_int
     lib.sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp]
     lib.sparse_attn_fwd.restype = C.c_int
+    lib.sparse_attn_fwd_static.argtypes = lib.sparse_attn_fwd.argtypes
+    lib.sparse_attn_fwd_static.restype = C.c_int
     lib.imbalance_ratio.argtypes = [vp, i32, i32, C.POINTER(C.c_double)]
     lib.imbalance_ratio.restype = C.c_int
     lib.dbsp_plan_get.argtypes = [vp, i32, C.POINTER(vp), i64p]
@@ -214,9 +216,12 @@ def _stream_ptr(stream):
     return C.c_void_p(stream.cuda_stream)
 
 
-def sparse_attn_fwd(plan: Plan, q, k, v, o=None, lse=None, softmax_scale: float = 0.0, stream=None, want_lse: bool = True):
+def sparse_attn_fwd(plan: Plan, q, k, v, o=None, lse=None, softmax_scale: float = 0.0, stream=None, want_lse: bool = True,
+                    static_scratch: bool = False):
     """q [B,H,Nq,d], k/v [B,H,Nk,d]: contiguous bf16 torch tensors on the GPU.  Enqueues on
-    `stream` (default: torch's current stream) and returns (o, lse) without synchronising."""
+    `stream` (default: torch's current stream) and returns (o, lse) without synchronising.
+    static_scratch=True calls sparse_attn_fwd_static (pass o and lse then: this wrapper allocates
+    the ones it is not given)."""
     import torch
     for name, x in (("q", q), ("k", k), ("v", v)):
         if x.dtype != torch.bfloat16 or not x.is_cuda or not x.is_contiguous() or x.dim() != 4:
@@ -230,9 +235,10 @@ def sparse_attn_fwd(plan: Plan, q, k, v, o=None, lse=None, softmax_scale: float 
     if lse is None and want_lse:
         lse = torch.empty((B, H, Nq), dtype=torch.float32, device=q.device)
     lse_ptr = C.c_void_p(lse.data_ptr()) if lse is not None else C.c_void_p(0)
-    _check(load_library().sparse_attn_fwd(plan.handle, C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
-                                          C.c_void_p(v.data_ptr()), C.c_void_p(o.data_ptr()), lse_ptr,
-                                          B, Nq, Nk, d, float(softmax_scale), _stream_ptr(stream)))
+    entry = load_library().sparse_attn_fwd_static if static_scratch else load_library().sparse_attn_fwd
+    _check(entry(plan.handle, C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+                 C.c_void_p(v.data_ptr()), C.c_void_p(o.data_ptr()), lse_ptr,
+                 B, Nq, Nk, d, float(softmax_scale), _stream_ptr(stream)))
     return o, lse
 
 

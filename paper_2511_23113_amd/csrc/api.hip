@@ -192,6 +192,31 @@ int upload(dbsp_plan* plan) {
   return DBSP_OK;
 }
 
+// ---- scratch for callers that cannot allocate ------------------------------------------------
+// The split-row partials of sparse_attn_fwd_static go here instead of into the plan's buffer.
+// One copy of the array exists per GPU the library runs on, for the life of the process; every
+// call on a GPU shares it.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the device address is looked up once per device and used from then on.
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;   // 32 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch` (the device must be current).
+int static_scratch(int device, unsigned char** out) {
+  if (device < 0 || device >= kMaxDevices) return fail(DBSP_EINVAL, "sparse_attn_fwd_static: device index out of range");
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr) return fail(DBSP_EHIP, "sparse_attn_fwd_static: the static scratch has no device address");
+    g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return DBSP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -316,27 +341,45 @@ void dbsp_plan_destroy(dbsp_plan* plan) {
   delete plan;
 }
 
-int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
-                    float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
-                    void* stream) {
-  if (!plan || !q || !k || !v || !o) return fail(DBSP_EINVAL, "sparse_attn_fwd: null pointer");
+static int forward(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
+                   float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
+                   void* stream, bool static_scratch_wanted, const char* who) {
+  const std::string w(who);
+  if (!plan || !q || !k || !v || !o) return fail(DBSP_EINVAL, w + ": null pointer");
   const dbsp_host_plan& hp = plan->host;
-  if (B <= 0) return fail(DBSP_EINVAL, "sparse_attn_fwd: B must be positive");
-  if (d != 64 && d != 128) return fail(DBSP_EINVAL, "sparse_attn_fwd: head dim must be 64 or 128");
-  if (hp.block != 64 && hp.block != 128) return fail(DBSP_EINVAL, "sparse_attn_fwd: the plan's block size must be 64 or 128");
+  if (B <= 0) return fail(DBSP_EINVAL, w + ": B must be positive");
+  if (d != 64 && d != 128) return fail(DBSP_EINVAL, w + ": head dim must be 64 or 128");
+  if (hp.block != 64 && hp.block != 128) return fail(DBSP_EINVAL, w + ": the plan's block size must be 64 or 128");
   if (Nq <= 0 || Nk <= 0 || Nq % hp.block != 0 || Nk % hp.block != 0)
-    return fail(DBSP_ESHAPE, "sparse_attn_fwd: sequence lengths must be positive multiples of the block size");
+    return fail(DBSP_ESHAPE, w + ": sequence lengths must be positive multiples of the block size");
   if (Nq / hp.block != hp.nQ || Nk / hp.block != hp.nK)
-    return fail(DBSP_ESHAPE, "sparse_attn_fwd: Nq/Nk do not match the plan's block grid");
-  if (!plan->dev.resident) return fail(DBSP_EINVAL, "sparse_attn_fwd: the plan was built host-only");
-  if (!(softmax_scale == softmax_scale)) return fail(DBSP_EINVAL, "sparse_attn_fwd: softmax_scale is NaN");
+    return fail(DBSP_ESHAPE, w + ": Nq/Nk do not match the plan's block grid");
+  if (!plan->dev.resident) return fail(DBSP_EINVAL, w + ": the plan was built host-only");
+  if (!(softmax_scale == softmax_scale)) return fail(DBSP_EINVAL, w + ": softmax_scale is NaN");
   int cur = -1;
   DBSP_HIP(hipGetDevice(&cur));
-  if (cur != plan->dev.device) return fail(DBSP_EINVAL, "sparse_attn_fwd: the plan lives on another device than the current one");
-  if (B > plan->dev.max_batch && hp.n_slots > 0)
-    return fail(DBSP_EINVAL, "sparse_attn_fwd: B exceeds the max_batch the plan's split-row scratch was sized for");
+  if (cur != plan->dev.device) return fail(DBSP_EINVAL, w + ": the plan lives on another device than the current one");
 
   const dbsp_device_plan& dv = plan->dev;
+  float* part_o = dv.part_o;
+  float* part_lse = dv.part_lse;
+  if (static_scratch_wanted) {
+    // partial outputs f32 [B][n_slots][block][d], then their LSE f32 [B][n_slots][block]
+    const size_t rows = (size_t)B * hp.n_slots * hp.block;
+    const size_t lse_off = (rows * d * sizeof(float) + 255) & ~size_t(255);
+    const size_t need = lse_off + rows * sizeof(float);
+    if (need > kStaticScratchBytes)
+      return fail(DBSP_EINVAL, w + ": the split rows of this plan need " + std::to_string(need) + " bytes of scratch for B = " +
+                                   std::to_string(B) + ", the static buffer holds " + std::to_string(kStaticScratchBytes));
+    unsigned char* base = nullptr;
+    const int rc = static_scratch(cur, &base);
+    if (rc != DBSP_OK) return rc;
+    part_o = reinterpret_cast<float*>(base);
+    part_lse = reinterpret_cast<float*>(base + lse_off);
+  } else if (B > dv.max_batch && hp.n_slots > 0) {
+    return fail(DBSP_EINVAL, w + ": B exceeds the max_batch the plan's split-row scratch was sized for");
+  }
+
   dbsp_fwd_params p;
   p.q = static_cast<const uint16_t*>(q);
   p.k = static_cast<const uint16_t*>(k);
@@ -351,8 +394,8 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
   p.empty_rows = dv.empty_rows;
   p.part_ptr = dv.part_ptr;
   p.part_items = dv.part_items;
-  p.part_o = dv.part_o;
-  p.part_lse = dv.part_lse;
+  p.part_o = part_o;
+  p.part_lse = part_lse;
   p.busy = dv.busy;
   p.hw_id = dv.hw_id;
   p.B = B; p.H = hp.H; p.nQ = hp.nQ; p.nK = hp.nK;
@@ -364,10 +407,22 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
   hipStream_t st = static_cast<hipStream_t>(stream);
   DBSP_HIP(hipStreamWaitEvent(st, static_cast<hipEvent_t>(dv.uploaded), 0));   // the plan's upload is asynchronous
   hipError_t e = dbsp_launch_fwd(p, hp.block, d, hp.P, st);
-  if (e != hipSuccess) return fail_hip(e, "sparse_attn_fwd launch");
+  if (e != hipSuccess) return fail_hip(e, (w + " launch").c_str());
   DBSP_HIP(hipEventRecord(static_cast<hipEvent_t>(dv.last_use), st));
   plan->dev.used = true;
   return DBSP_OK;
+}
+
+int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
+                    float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
+                    void* stream) {
+  return forward(plan, q, k, v, o, lse, B, Nq, Nk, d, softmax_scale, stream, false, "sparse_attn_fwd");
+}
+
+int sparse_attn_fwd_static(const dbsp_plan* plan, const void* q, const void* k, const void* v, void* o,
+                           float* lse, int32_t B, int32_t Nq, int32_t Nk, int32_t d, float softmax_scale,
+                           void* stream) {
+  return forward(plan, q, k, v, o, lse, B, Nq, Nk, d, softmax_scale, stream, true, "sparse_attn_fwd_static");
 }
 
 int imbalance_ratio(const int64_t* work, int32_t periods, int32_t partitions, double* rho_out) {
