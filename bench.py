@@ -23,10 +23,33 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
 
-# HBM-side bytes per launch of dbsp_fwd_kernel (default placement), from rocprofv3 --pmc runs of this
-# command: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy
-# (see profiles/dbsp_fwd_kernel_wan480p_pmc.md).  Keyed by workload config; null when not measured.
-MEASURED_TRAFFIC = {3: 12.8e9}
+# HBM-side bytes per launch of dbsp_fwd_kernel come from rocprofv3 --pmc runs of this command
+# (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy).  They are not
+# measured in this run: the line reports what the tracked counter summary states, together with the
+# file and the commit it was taken at, or null when there is no summary for the workload.
+TRAFFIC_SUMMARY = {3: "profiles/dbsp_fwd_kernel_config3_pmc.md", 2: "profiles/dbsp_fwd_kernel_config2_pmc.md",
+                   5: "profiles/dbsp_fwd_kernel_config5_pmc.md"}
+
+
+def recorded_traffic(cfg):
+    """(bytes per launch, {"file", "commit"}) from the summary's line
+    `roofline.traffic: <bytes> bytes per launch, measured at commit <hash>`; (None, None) if absent."""
+    import re
+    path = TRAFFIC_SUMMARY.get(cfg)
+    if not path or not os.path.exists(os.path.join(ROOT, path)):
+        return None, None
+    m = re.search(r"roofline\.traffic:\s*([0-9.eE+]+)\s*bytes per launch, measured at commit\s+([0-9a-f]{7,40})",
+                  open(os.path.join(ROOT, path)).read())
+    if not m:
+        return None, None
+    return float(m.group(1)), {"file": path, "commit": m.group(2)}
+
+
+def algorithmic_bytes(mask, block, d, B=1):
+    """What the method must move if nothing is reused: K and V of every active pair, Q and O of every non-empty row, LSE."""
+    pairs = int((mask != 0).sum())
+    rows = int(((mask != 0).sum(2) > 0).sum())
+    return B * (pairs * 4.0 * block * d + rows * (4.0 * block * d + 4.0 * block))
 
 
 def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
@@ -59,39 +82,128 @@ def cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=15.0):
                       f"{t_used:.1f} s of float64 numpy; throughput extrapolated by active-block count"}
 
 
+def timed_launches(dbsp, torch, plan, qq, kk, vv, oo, ll, reps=3, warm=2):
+    """Mean time of `reps` launches (HIP events on the launch stream), after `warm` untimed ones."""
+    for _ in range(warm):
+        dbsp.sparse_attn_fwd(plan, qq, kk, vv, o=oo, lse=ll)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dbsp.sparse_attn_fwd(plan, qq, kk, vv, o=oo, lse=ll)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def busy_rho_per_cu(np, plan):
+    ticks, hw = plan.busy()
+    percu = {}
+    for tk, idv in zip(ticks.tolist(), hw.tolist()):
+        percu[idv] = percu.get(idv, 0) + tk
+    vals = np.array(list(percu.values()), dtype=np.float64)
+    return (float(vals.max() / vals.mean()) if vals.sum() > 0 else 1.0), len(percu)
+
+
+def low_density_heads(dbsp, torch, np, c, mask, q, k, v, o, lse, plan_kw):
+    """The low-density heads of the workload on their own (extra launches): few rows share a KV block
+    there, so the memory rate is what counts; reported as algorithmic bytes per second."""
+    block, d = c["block"], c["d"]
+    dens = (mask != 0).mean(axis=(1, 2))
+    low = np.where(dens < 0.12)[0]
+    if not len(low):
+        return None
+    m2 = mask.copy()
+    m2[[h for h in range(mask.shape[0]) if h not in set(low.tolist())]] = 0
+    plan = dbsp.plan_sparse_attn(m2, block, **plan_kw)
+    ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=5)
+    plan.close()
+    pairs = int((m2 != 0).sum())
+    return {"heads": low.tolist(), "density": [round(float(x), 4) for x in dens[low]], "active_blocks": pairs,
+            "kernel_ms": ms, "algorithmic_GB_per_s": algorithmic_bytes(m2, block, d) / (ms * 1e-3) / 1e9,
+            "tflops": pairs * 4.0 * block * block * d / (ms * 1e-3) / 1e12}
+
+
+def other_config(dbsp, synth, torch, np, cfg, plan_kw):
+    """One of the other workload configs under the same placement options: kernel time, fraction of the
+    bf16 MFMA peak, algorithmic bytes per second, planning time, busy-time imbalance (extra launches)."""
+    c = synth.config_shape(cfg)
+    block, d, B = c["block"], c["d"], c["B"]
+    mask = synth.mask_for_config(cfg)
+    qb, kb, vb = synth.qkv_for_config(cfg, B, c["H"], c["Nq"], c["Nk"], d)
+    dev = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    q, k, v = dev(qb), dev(kb), dev(vb)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, c["H"], c["Nq"]), dtype=torch.float32, device="cuda")
+    plan_ms = []
+    for _ in range(4):
+        plan = dbsp.plan_sparse_attn(mask, block, **plan_kw)
+        plan_ms.append(plan.stats(with_rho=False)["plan_usec"] / 1e3)
+        if _ < 3:
+            plan.close()
+    ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=5 if cfg != 4 else 3)
+    rho_busy, _ = busy_rho_per_cu(np, plan)
+    st = plan.stats()
+    plan.close()
+    nnz = int((mask != 0).sum())
+    flops = float(B) * nnz * 4.0 * block * block * d
+    del q, k, v, o, lse
+    torch.cuda.empty_cache()
+    return {"workload": f"config {cfg}: {c['name']} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={d} block={block}", "active_blocks": nnz,
+            "kernel_ms": ms, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "algorithmic_GB_per_s": algorithmic_bytes(mask, block, d, B) / (ms * 1e-3) / 1e9,
+            "plan_ms": float(np.median(plan_ms)), "rho_busy_per_cu": rho_busy,
+            "rho_s_planned": {"naive": st["rho_naive"], "balanced": st["rho_balanced"], "timed": st["rho_plan"]}}
+
+
+def speedup_sweep(dbsp, synth, torch, np, q, k, v, o, lse, plan_kw, targets=(1.0, 1.25, 1.5, 2.0, 2.5, 3.0)):
+    """Kernel time under the naive placement against the balanced one, over masks of the workload's
+    shape whose imbalance under the naive placement is dialled from about 1 to about 3 (the one-GPU
+    form of the paper's attention speed-up against imbalance ratio experiment)."""
+    rows = []
+    for tgt in targets:
+        m = synth.imbalance_sweep_mask(tgt)
+        res = {"target": tgt, "active_blocks": int((m != 0).sum())}
+        for name, kw in (("naive", dict(mode=dbsp.MODE_NAIVE)), ("balanced", plan_kw)):
+            plan = dbsp.plan_sparse_attn(m, 128, **kw)
+            res[name + "_ms"] = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=3)
+            res["rho_busy_" + name], _ = busy_rho_per_cu(np, plan)
+            st = plan.stats()
+            res["rho_s_naive"] = st["rho_naive"]
+            res["rho_s_" + name] = st["rho_plan"]
+            plan.close()
+        res["speedup"] = res["naive_ms"] / res["balanced_ms"]
+        rows.append(res)
+    return rows
+
+
+def placement_sweep(dbsp, torch, np, mask, block, q, k, v, o, lse):
+    """The locality / balance trade-off on the workload: the round-based placement over the number of
+    locality groups G, and the greedy placement with the paper's reward factor R_b over R_b and G.
+    Three launches each (the first untimed), in the order listed: a rocprofv3 --pmc run of this command
+    sees the dbsp_fwd_kernel dispatches in that order."""
+    variants = [("greedy", dict(mode=dbsp.MODE_BALANCED))]
+    variants += [(f"rounds G={g}", dict(mode=dbsp.MODE_ROUNDS, locality_groups=g)) for g in (1, 2, 4, 8, 16, 32)]
+    variants += [(f"reward G=8 R_b={r}", dict(mode=dbsp.MODE_REWARD, locality_groups=8, reward=r)) for r in (0.0, 0.25, 0.5, 1.0, 2.0, 8.0)]
+    variants += [(f"reward G={g} R_b=1.0", dict(mode=dbsp.MODE_REWARD, locality_groups=g, reward=1.0)) for g in (1, 2, 4, 16, 32)]
+    rows = []
+    for name, kw in variants:
+        plan = dbsp.plan_sparse_attn(mask, block, **kw)
+        ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=2, warm=1)
+        rho_busy, _ = busy_rho_per_cu(np, plan)
+        rows.append({"placement": name, "rho_s": plan.stats(with_rho=False)["rho_plan"], "kernel_ms": ms, "rho_busy_per_cu": rho_busy,
+                     "launches": 3})
+        plan.close()
+    return rows
+
+
 def extras(dbsp, synth, torch, np, cfg, c, mask, q, k, v, o, lse):
     """Side measurements (not part of the timed region)."""
     res = {}
 
     def timed(plan, qq, kk, vv, oo, ll, reps=3):
-        for _ in range(2):
-            dbsp.sparse_attn_fwd(plan, qq, kk, vv, o=oo, lse=ll)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            dbsp.sparse_attn_fwd(plan, qq, kk, vv, o=oo, lse=ll)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+        return timed_launches(dbsp, torch, plan, qq, kk, vv, oo, ll, reps=reps)
 
-    # (1) low-density heads of this config on their own: little KV reuse, so the memory rate is what counts
-    block, d = c["block"], c["d"]
-    dens = (mask != 0).mean(axis=(1, 2))
-    low = np.where(dens < 0.12)[0]
-    if len(low):
-        m2 = mask.copy()
-        m2[[h for h in range(mask.shape[0]) if h not in set(low.tolist())]] = 0
-        plan = dbsp.plan_sparse_attn(m2, block, mode=dbsp.MODE_ROUNDS, locality_groups=8)
-        ms = timed(plan, q, k, v, o, lse)
-        pairs = int((m2 != 0).sum())
-        rows = int(((m2 != 0).sum(2) > 0).sum())
-        alg_bytes = pairs * 4.0 * block * d + rows * (4.0 * block * d + 4.0 * block)       # K+V per pair; Q, O, LSE per row
-        res["low_density_heads"] = {"heads": low.tolist(), "density": [round(float(x), 4) for x in dens[low]], "active_blocks": pairs,
-                                    "kernel_ms": ms, "algorithmic_GB_per_s": alg_bytes / (ms * 1e-3) / 1e9,
-                                    "tflops": pairs * 4.0 * block * block * d / (ms * 1e-3) / 1e12}
-        plan.close()
-
-    # (2) kernel time against the number of active blocks: the cost of a mask is its dense-block count
+    # kernel time against the number of active blocks: the cost of a mask is its dense-block count
     # (paper: Background, "Block-wise Sparse Attention"), so this should be a straight line.  The masks are
     # config 5's first mask restricted to its first 1..H heads, then the first masks of its sequence.
     c5 = synth.config_shape(5)
@@ -139,10 +251,20 @@ def main():
     ap.add_argument("--locality-groups", type=int, default=8,
                     help="round-based placement: keep runs of neighbouring query blocks inside one of G groups of partitions "
                          "(partition p is in group p mod G; 8 = the XCDs of an MI355X, each with its own L2); 0 or 1 = one group")
+    ap.add_argument("--dynamic-tail", type=int, default=40,
+                    help="permille of the work left to the queue all workgroups share (taken at run time by whoever runs out of "
+                         "placed work); 0 = everything placed")
+    ap.add_argument("--no-side-measurements", action="store_true",
+                    help="leave out the low-density heads and the other workload configs (extra launches after the timed region): "
+                         "for profiler runs that should see the timed launches only")
+    ap.add_argument("--speedup-sweep", action="store_true",
+                    help="also time the naive against the balanced placement over masks whose imbalance is dialled from 1 to 3")
+    ap.add_argument("--placement-sweep", action="store_true",
+                    help="also time the round-based placement over the number of locality groups and the reward-biased greedy over R_b")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the few-millisecond measurement of the chip's sustained MFMA rate")
     ap.add_argument("--extras", action="store_true",
-                    help="also measure (extra launches, outside the timed region) kernel time against active-block count over the 50 "
-                         "masks of config 5, and the memory rate of the low-density heads of this config run on their own")
+                    help="also measure (extra launches, outside the timed region) kernel time against active-block count over "
+                         "masks of config 5")
     ap.add_argument("--zero-data", action="store_true",
                     help="power experiment, not the benchmark: all-zero Q, K, V (same instruction stream and cycle count, far fewer "
                          "bit flips, so the chip holds a higher clock)")
@@ -191,18 +313,17 @@ def main():
         except dbsp.DbspError as exc:              # a diagnostic only: never fail the benchmark over it
             print(f"bench.py: MFMA probe failed: {exc}", file=sys.stderr)
 
+    def plan_kw(mode):
+        rounds = mode == dbsp.MODE_ROUNDS
+        return dict(num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead,
+                    locality_groups=args.locality_groups if rounds else 0, dynamic_tail=args.dynamic_tail if rounds else 0,
+                    partition_cost=part_cost["v"] if mode != dbsp.MODE_NAIVE else None)
+
     def one_plan(mode):
-        return dbsp.plan_sparse_attn(mask, block, num_partitions=args.partitions, mode=mode, item_overhead=args.item_overhead,
-                                     locality_groups=args.locality_groups if mode == dbsp.MODE_ROUNDS else 0,
-                                     partition_cost=part_cost["v"] if mode != dbsp.MODE_NAIVE else None)
+        return dbsp.plan_sparse_attn(mask, block, **plan_kw(mode))
 
     def measured_rho(plan):
-        ticks, hw = plan.busy()
-        percu = {}
-        for tk, idv in zip(ticks.tolist(), hw.tolist()):
-            percu[idv] = percu.get(idv, 0) + tk
-        vals = np.array(list(percu.values()), dtype=np.float64)
-        return float(vals.max() / vals.mean()) if vals.sum() > 0 else 1.0, len(percu)
+        return busy_rho_per_cu(np, plan)
 
     # placements: planned rho_s (Eq. 1 on block counts) of the naive, the greedy longest-first and the
     # round-based placement come from the planner alone; kernel times and busy-time imbalance of all
@@ -264,7 +385,7 @@ def main():
         dbsp.sparse_attn_fwd(plan, q, k, v, o=o, lse=lse)
         if timed:
             ev[i][1].record()
-            plan_us.append(plan.stats()["plan_usec"])
+            plan_us.append(plan.stats(with_rho=False)["plan_usec"])
         if static_plan is None:
             plans.append(plan)
             if len(plans) > 2:          # released two steps later (freeing device memory waits for the device)
@@ -307,6 +428,8 @@ def main():
 
     value = flops * args.steps / total_s / 1e12
     kern_tflops = flops / (kern_avg * 1e-3) / 1e12
+    default_launch = args.locality_groups == 8 and args.partitions == 0 and args.dynamic_tail == 40 and not args.zero_data
+    traffic, traffic_src = recorded_traffic(cfg) if default_launch else (None, None)
     out = {
         "metric": "block-sparse attention effective TFLOPS over active blocks (4*b^2*d per active block pair)",
         "value": value,
@@ -323,7 +446,8 @@ def main():
         "config": {"workload": f"config {cfg}: {c['name']} B={B} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={d} block={block}, "
                                f"nnz={nnz} active blocks (density {nnz / mask.size:.3f})",
                    "step": "plan_sparse_attn + sparse_attn_fwd" if static_plan is None else "sparse_attn_fwd (plan reused)",
-                   "partitions": hst["num_partitions"], "placement": "rounds", "locality_groups": max(1, args.locality_groups)},
+                   "partitions": hst["num_partitions"], "placement": "rounds", "locality_groups": max(1, args.locality_groups),
+                   "dynamic_tail_permille": args.dynamic_tail},
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "kernel_ms": kern_avg,
         "kernel_ms_min": float(np.min(kern_ms)),
@@ -337,15 +461,31 @@ def main():
                                                                           "unit": "1024 = mean time per block"},
                       **({"compare": side} if side else {})},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(cfg) if (args.locality_groups == 8 and args.partitions == 0 and not args.zero_data) else None,
+                     "frac": kern_tflops / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": "dbsp_fwd_kernel", "flops_per_launch": flops,
+                     "algorithmic_bytes_per_launch": algorithmic_bytes(mask, block, d, B),
+                     "algorithmic_GB_per_s": algorithmic_bytes(mask, block, d, B) / (kern_avg * 1e-3) / 1e9,
                      **({"sustained_mfma_only": {**sustained, "frac_of_sustained": kern_tflops / sustained["mfma_tflops"]}}
                         if sustained else {})},
     }
     if cost is not None:
         out["cost_model"] = cost
+    kw_timed = plan_kw(dbsp.MODE_ROUNDS)
+    if not args.no_side_measurements:
+        ld = low_density_heads(dbsp, torch, np, c, mask, q, k, v, o, lse, kw_timed)
+        if ld is not None:
+            out["low_density_heads"] = ld
+    if args.speedup_sweep and cfg == 3:
+        out["speedup_vs_imbalance"] = speedup_sweep(dbsp, synth, torch, np, q, k, v, o, lse, kw_timed)
+    if args.placement_sweep:
+        out["placement_sweep"] = placement_sweep(dbsp, torch, np, mask, block, q, k, v, o, lse)
     if args.extras:
         out["extras"] = extras(dbsp, synth, torch, np, cfg, c, mask, q, k, v, o, lse)
+    if not args.no_side_measurements:
+        del q, k, v, o, lse
+        torch.cuda.empty_cache()
+        kw_other = dict(kw_timed, num_partitions=0, partition_cost=None)
+        out["other_configs"] = [other_config(dbsp, synth, torch, np, oc, kw_other) for oc in (2, 4, 5) if oc != cfg]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, c, mask, qb, kb, vb, budget_s=args.cpu_budget)
     print(json.dumps(out))

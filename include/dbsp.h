@@ -41,7 +41,7 @@ typedef enum dbsp_status {
 /* Opaque, library-owned plan.  Immutable after creation except for its scratch buffers. */
 typedef struct dbsp_plan dbsp_plan;
 
-enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1, DBSP_MODE_ROUNDS = 2 };
+enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1, DBSP_MODE_ROUNDS = 2, DBSP_MODE_REWARD = 3 };
 enum { DBSP_PLAN_HOST_ONLY = 1 }; /* flags bit: build the plan on the host only (no device, no upload);
                                      such a plan cannot be passed to sparse_attn_fwd */
 
@@ -56,7 +56,14 @@ typedef struct dbsp_plan_opts {
                              rounds of P, and inside a round the k-th heaviest item goes to the k-th
                              least-loaded partition.  All partitions then work on the same head at about
                              the same time, so KV blocks are reused from L2: balance traded for locality,
-                             the trade-off the paper steers with its reward factor R_b */
+                             the trade-off the paper steers with its reward factor R_b;
+                             DBSP_MODE_REWARD: the greedy longest-first placement with the paper's reward factor
+                             itself (Methodology, "Block-level Partitioning", overhead mitigation; Alg. 1, second
+                             loop): partition p belongs to group p mod locality_groups (the compute units behind
+                             one L2), an item's home group is q_block * G / nQ (neighbouring query blocks, which
+                             share KV blocks, have one home), and before each argmin the accumulated load of
+                             every partition of the home group is lowered by reward * (the item's weight),
+                             compared in double; ties go to the lowest partition index */
   int32_t max_item_len;   /* split threshold in blocks: a row with more active blocks is cut into
                              ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (2 P)); < 0 -> never split */
   int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
@@ -77,6 +84,15 @@ typedef struct dbsp_plan_opts {
   int32_t max_batch;      /* >= 0; the largest B sparse_attn_fwd will be called with on this plan (0 -> 1).  Rows
                              that are split need device scratch per batch entry; it is allocated here, at plan
                              time, so that the forward call never allocates or waits */
+  int32_t dynamic_tail;   /* DBSP_MODE_ROUNDS only, permille in [0, 1000): the end of the item sequence -- the longest
+                             suffix whose weight is at most dynamic_tail / 1000 of the total, plus whatever a partial
+                             last round would hold -- is placed on no partition: the workgroups take those items from
+                             a shared queue, one by one, as they run out of placed work.  This is the greedy rule
+                             ("each unit to the least-loaded partition", Alg. 1's first loop) decided at run time,
+                             with real finishing times as loads; it absorbs speed differences between compute
+                             units.  Heads come in descending order of block count, so the queue holds the lightest
+                             rows.  Results do not depend on who computes an item.  0 = everything placed */
+  double reward;          /* DBSP_MODE_REWARD only: R_b >= 0 (0 = plain greedy) */
 } dbsp_plan_opts;
 
 /*
@@ -261,7 +277,9 @@ enum dbsp_plan_array {
   DBSP_PART_LOAD = 7,       /* int64 [P]         active blocks per partition (pure block counts)      */
   DBSP_BLOCKS_PER_HEAD = 8, /* int64 [H]         active blocks per head                               */
   DBSP_ROW_CNT = 9,         /* int32 [H*nQ]      active blocks per row                                */
-  DBSP_EMPTY_ROWS = 10      /* int32 [n_empty]   rows with no active block                            */
+  DBSP_EMPTY_ROWS = 10,     /* int32 [n_empty]   rows with no active block                            */
+  DBSP_TAIL_ITEMS = 11      /* int32 [n_tail]    items left to the shared queue (dynamic_tail), in queue order;
+                               they appear in no partition's list, and PART_LOAD / rho_plan leave them out */
 };
 
 /* dbsp_plan_get: *data points to the array, *count is its number of ELEMENTS of the type above. */
@@ -285,6 +303,12 @@ int dbsp_plan_stats(const dbsp_plan* plan, double* rho_naive, double* rho_balanc
  * half up), clamped to [512, 2048]; 1024 for a partition without work or measurement.  Synchronises
  * `stream` before reading.  Errors: DBSP_EINVAL (null pointer, host-only plan), DBSP_EHIP. */
 int dbsp_plan_calibrate(const dbsp_plan* plan, int32_t* cost, void* stream);
+
+/* dbsp_plan_tail_takes: how often each item of the shared queue (DBSP_TAIL_ITEMS) has been taken since the plan was
+ * made: after n forward calls with batch size B every entry must read n * B (each item taken exactly once per batch
+ * entry and launch).  takes: host, uint32 [n_tail], written.  Synchronises `stream` before reading.
+ * Errors: DBSP_EINVAL (null pointer, host-only plan), DBSP_EHIP. */
+int dbsp_plan_tail_takes(const dbsp_plan* plan, uint32_t* takes, void* stream);
 
 /* dbsp_plan_busy: per-partition busy time of the LAST sparse_attn_fwd on this plan.
  * busy_ticks: host, uint64 [P], ticks of the 100 MHz constant clock summed over the partition's

@@ -34,6 +34,7 @@ import numpy as np
 MODE_BALANCED = 0
 MODE_NAIVE = 1
 MODE_ROUNDS = 2
+MODE_REWARD = 3
 
 
 def row_counts(mask):
@@ -136,7 +137,33 @@ def naive_partition(n_items: int, P: int):
     return [i // run for i in range(n_items)]
 
 
-def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int = 1, cost=None):
+def dynamic_tail_length(seq, weights, permille: int) -> int:
+    """Number of items at the end of the sequence `seq` that are left to a shared queue instead
+    of being placed: the longest suffix whose weight is at most permille/1000 of the total
+    weight (integer arithmetic: total * permille // 1000).  The compute units take those items
+    one by one as they run out of placed work, which is the greedy rule of Alg. 1's first loop
+    ("each unit to the least-loaded partition") decided at run time, with the measured
+    finishing times as the loads.  Heads come in descending order of their block count, so the
+    suffix holds the lightest rows: the last item taken is a short one."""
+    budget = sum(weights) * int(permille) // 1000
+    n, acc = 0, 0
+    for i in reversed(seq):
+        if acc + weights[i] > budget:
+            break
+        acc += weights[i]
+        n += 1
+    return n
+
+
+def static_length(n_items: int, tail: int, P: int) -> int:
+    """Items that are placed when `tail` items would go to the shared queue: the rest, cut back
+    to whole rounds of P (a partial last round would leave the placed loads uneven by an item;
+    its items join the queue instead)."""
+    n_static = n_items - tail
+    return n_static - n_static % P if tail > 0 else n_static
+
+
+def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int = 1, cost=None, tail_permille: int = 0):
     """Round-based greedy placement (locality-preserving variant of the greedy of Alg. 1).
 
     Heads are taken in descending order of their dense-block count (Alg. 1's sort of
@@ -154,6 +181,8 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int =
     load that has not received a chunk in this round (ties: lowest index).  Inside its group
     a chunk is spread as before: k-th heaviest item to the group's k-th least-loaded partition.
     With cost[g] given (see lpt_partition) "load" is accumulated time, weight * cost[g], everywhere.
+    With tail_permille > 0 the items of the sequence past static_length(...) are not placed
+    (assignment -1): they form the shared queue.
     Returns (assignment per item, the item sequence).
     """
     cost = [1] * P if cost is None else [int(x) for x in cost]
@@ -165,11 +194,12 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int =
     for i, h in enumerate(item_heads):
         by_head[h].append(i)
     seq = [i for h in head_order for i in by_head[h]]
-    assign = [0] * len(weights)
+    n_static = static_length(len(seq), dynamic_tail_length(seq, weights, tail_permille) if tail_permille > 0 else 0, P)
+    assign = [-1] * len(weights)
     load = [0] * P
     per = P // groups
-    for r0 in range(0, len(seq), P):
-        rnd = seq[r0:r0 + P]
+    for r0 in range(0, n_static, P):
+        rnd = seq[r0:min(r0 + P, n_static)]
         chunks = [rnd[j * per:(j + 1) * per] for j in range(groups)]
         chunk_order = sorted(range(groups), key=lambda j: -sum(weights[i] for i in chunks[j]))
         free = list(range(groups))
@@ -182,6 +212,34 @@ def rounds_partition(item_heads, weights, blocks_per_head, P: int, groups: int =
                 assign[i] = parts[k]
                 load[parts[k]] += weights[i] * cost[parts[k]]
     return assign, seq
+
+
+def reward_partition(q_blocks, weights, nQ: int, P: int, groups: int, reward: float):
+    """Greedy longest-first placement with the paper's reward factor R_b (Methodology,
+    "Block-level Partitioning", overhead mitigation; Alg. 1, second loop): before the argmin the
+    accumulated load of the unit's initial GPU is lowered by R_b times the unit's own count, so a
+    unit stays where its data already is unless another GPU is clearly less loaded.
+
+    Carried onto one GPU: partition p belongs to group p mod G (the compute units behind one
+    L2); the "initial" group of an item is that of its query block under the contiguous layout,
+    q_block * G // nQ, so neighbouring query blocks, which share most of their KV blocks, prefer
+    one L2.  Every partition of the home group gets the reward.  Items are taken in descending
+    weight order (stable); the biased loads  load[p] - reward * weight  (home group) or
+    load[p]  (elsewhere) are compared in float64; first minimum wins (lowest partition index).
+    Returns the assignment per item."""
+    if groups < 1 or P % groups != 0:
+        raise ValueError("groups must divide the number of partitions")
+    group_of = np.arange(P) % groups
+    load = np.zeros(P, dtype=np.int64)
+    assign = [0] * len(weights)
+    for i in sorted(range(len(weights)), key=lambda j: -weights[j]):
+        home = int(q_blocks[i]) * groups // nQ
+        biased = load.astype(np.float64)
+        biased[group_of == home] -= float(reward) * float(weights[i])
+        p = int(np.argmin(biased))
+        assign[i] = p
+        load[p] += int(weights[i])
+    return assign
 
 
 def imbalance_ratio(work):
@@ -212,7 +270,7 @@ def carry_over_partition(previous, items, nQ: int, P: int):
     The paper carries a head -> GPU map over; here the unit is a work item, named by its row
     and its ordinal among that row's items.  An item the previous plan also had keeps that
     item's partition.  The others (a row that was empty before, or that is now cut into more
-    pieces) are taken in item order, each going to the partition with the least load in blocks
+    pieces, or whose item the previous plan had left to its shared queue) are taken in item order, each going to the partition with the least load in blocks
     (lowest index on ties), after all carried-over items are in place.
     Returns (assign, loads)."""
     prev_part = {}
@@ -224,7 +282,7 @@ def carry_over_partition(previous, items, nQ: int, P: int):
     for i, (h, qb, _, _) in enumerate(previous["items"]):
         t = ordinal.get((h, qb), 0)
         ordinal[(h, qb)] = t + 1
-        by_key[(h, qb, t)] = prev_part[i]
+        by_key[(h, qb, t)] = prev_part.get(i)      # None: the item sat in the previous plan's shared queue
     assign = [None] * len(items)
     loads = [0] * P
     ordinal = {}
@@ -244,11 +302,16 @@ def carry_over_partition(previous, items, nQ: int, P: int):
 
 
 def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0,
-         previous=None, reuse_threshold: float = 1.0, locality_groups: int = 1, partition_cost=None):
+         previous=None, reuse_threshold: float = 1.0, locality_groups: int = 1, partition_cost=None,
+         dynamic_tail: int = 0, reward: float = 0.0):
     """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly).
 
     With `previous` (a plan of the same geometry and P), the previous placement is kept when the
-    new mask's rho_s under it is <= reuse_threshold; `reused` and `rho_reuse` report the outcome."""
+    new mask's rho_s under it is <= reuse_threshold; `reused` and `rho_reuse` report the outcome.
+    dynamic_tail (permille of the total weight, round-based placement only, not with a carried-over
+    placement): the end of the item sequence goes to `tail_items`, a queue shared by all partitions,
+    and is in no partition's list; part_load and rho_plan then cover the placed items only.
+    reward (MODE_REWARD only): the paper's R_b, see reward_partition."""
     mask = np.asarray(mask)
     H, nQ, nK = mask.shape
     cnt, per_head, total = row_counts(mask)
@@ -264,7 +327,8 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     def loads_of(assign):
         ld = [0] * P
         for i, g in enumerate(assign):
-            ld[g] += lens[i]
+            if g >= 0:
+                ld[g] += lens[i]
         return ld
 
     rho_bal = imbalance_ratio([loads_of(lpt_assign)])
@@ -281,14 +345,19 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
         assign = lpt_assign
     elif mode == MODE_NAIVE:
         assign = nv_assign
+    elif mode == MODE_REWARD:
+        assign = reward_partition([it[1] for it in items], weights, nQ, P, max(1, locality_groups), reward)
     else:
-        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P, max(1, locality_groups), partition_cost)
+        assign, order = rounds_partition([it[0] for it in items], weights, per_head, P, max(1, locality_groups), partition_cost,
+                                         tail_permille=dynamic_tail)
+    tail_items = [i for i in order if assign[i] < 0]
 
     # per-partition lists: ascending item id = ascending (head, q_block, kv_begin); for the
     # round-based placement, the order of the rounds
     lists = [[] for _ in range(P)]
     for i in order:
-        lists[assign[i]].append(i)
+        if assign[i] >= 0:
+            lists[assign[i]].append(i)
     part_ptr = [0]
     part_items = []
     for g in range(P):
@@ -300,7 +369,7 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
         cnt=cnt, blocks_per_head=per_head, nnz=total,
         row_ptr=row_ptr, kv_idx=kv_idx,
         items=items, item_slot=slot, split_rows=split_rows,
-        part_ptr=part_ptr, part_items=part_items,
+        part_ptr=part_ptr, part_items=part_items, tail_items=tail_items,
         part_load=loads_of(assign),
         rho_naive=rho_naive, rho_balanced=rho_bal, rho_plan=imbalance_ratio([loads_of(assign)]),
         reused=reused, rho_reuse=rho_reuse,

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     DbspError,
     MODE_BALANCED,
     MODE_NAIVE,
+    MODE_REWARD,
     MODE_ROUNDS,
     Plan,
     fit_cost_model,

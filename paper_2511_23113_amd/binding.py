@@ -15,15 +15,15 @@ import numpy as np
 from . import build as _build
 
 DBSP_OK, DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM, DBSP_EHIP = 0, -1, -2, -3, -4
-MODE_BALANCED, MODE_NAIVE, MODE_ROUNDS = 0, 1, 2
+MODE_BALANCED, MODE_NAIVE, MODE_ROUNDS, MODE_REWARD = 0, 1, 2, 3
 PLAN_HOST_ONLY = 1
 
-ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, BLOCKS_PER_HEAD, ROW_CNT, EMPTY_ROWS = range(11)
+ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, BLOCKS_PER_HEAD, ROW_CNT, EMPTY_ROWS, TAIL_ITEMS = range(12)
 _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 
 EXPORTS = (
     "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "sparse_attn_fwd_static", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
-    "dbsp_plan_busy", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
+    "dbsp_plan_busy", "dbsp_plan_tail_takes", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
     "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model", "dbsp_mfma_probe",
 )
 
@@ -37,7 +37,7 @@ class DbspError(RuntimeError):
 class PlanOpts(C.Structure):
     _fields_ = [("num_partitions", C.c_int32), ("mode", C.c_int32), ("max_item_len", C.c_int32),
                 ("item_overhead", C.c_int32), ("flags", C.c_int32), ("locality_groups", C.c_int32),
-                ("partition_cost", C.c_void_p), ("max_batch", C.c_int32)]
+                ("partition_cost", C.c_void_p), ("max_batch", C.c_int32), ("dynamic_tail", C.c_int32), ("reward", C.c_double)]
 
 
 _lib = None
@@ -84,6 +84,8 @@ def load_library(path: str | None = None):
     lib.dbsp_plan_stats.restype = C.c_int
     lib.dbsp_plan_busy.argtypes = [vp, vp, vp, vp]
     lib.dbsp_plan_busy.restype = C.c_int
+    lib.dbsp_plan_tail_takes.argtypes = [vp, vp, vp]
+    lib.dbsp_plan_tail_takes.restype = C.c_int
     lib.dbsp_plan_destroy.argtypes = [vp]
     lib.dbsp_plan_destroy.restype = None
     lib.dbsp_last_error.argtypes = []
@@ -143,6 +145,13 @@ class Plan:
                                              hw.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
         return ticks, hw
 
+    def tail_takes(self, stream=None):
+        """How often each item of the shared queue was taken since the plan was made (uint32 [n_tail]); synchronises."""
+        n = int(self.array(TAIL_ITEMS).shape[0])
+        takes = np.zeros(n, dtype=np.uint32)
+        _check(load_library().dbsp_plan_tail_takes(self.handle, takes.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
+        return takes
+
     def calibrate(self, stream=None):
         """Relative time per block of every partition in the last forward call (int32 [P], mean about 1024):
         pass it as partition_cost to later plans with the same partition count.  Synchronises."""
@@ -164,7 +173,8 @@ class Plan:
 
 def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
                      max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False,
-                     locality_groups: int = 0, partition_cost=None, max_batch: int = 0) -> Plan:
+                     locality_groups: int = 0, partition_cost=None, max_batch: int = 0, dynamic_tail: int = 0,
+                     reward: float = 0.0) -> Plan:
     """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.ndim != 3:
@@ -177,7 +187,7 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
     opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
-                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch)
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, float(reward))
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
     return Plan(out.value, H, nQ, nK, block)
@@ -185,7 +195,7 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
 
 def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,
                            max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False, locality_groups: int = 0,
-                           partition_cost=None, max_batch: int = 0):
+                           partition_cost=None, max_batch: int = 0, dynamic_tail: int = 0):
     """Plan the next mask of a sequence, keeping `previous`'s placement while rho_s under it stays
     <= reuse_threshold (see dbsp.h: plan_sparse_attn_reuse).  Returns (Plan, reused, rho_under_previous)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
@@ -198,7 +208,7 @@ def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_par
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
     opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
-                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch)
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, 0.0)
     out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
     _check(load_library().plan_sparse_attn_reuse(previous.handle, mask.ctypes.data_as(C.c_void_p), C.byref(opts),
                                                  float(reuse_threshold), C.byref(out), C.byref(reused), C.byref(rho)))

@@ -135,15 +135,17 @@ int upload(dbsp_plan* plan) {
   dbsp_host_plan& hp = plan->host;
   dbsp_device_plan& dv = plan->dev;
   const std::vector<int32_t>* arrays[] = {&hp.row_ptr,    &hp.items,      &hp.item_slot, &hp.split_rows,
-                                          &hp.empty_rows, &hp.part_ptr,   &hp.part_items};
-  constexpr int NA = 7;
+                                          &hp.empty_rows, &hp.part_ptr,   &hp.part_items, &hp.tail_items};
+  constexpr int NA = 8;
   size_t off[NA + 1];   // in int32 units, each array 16-byte aligned
   off[0] = 0;
   for (int i = 0; i < NA; ++i) off[i + 1] = off[i] + ((arrays[i]->size() + 3) & ~size_t(3));
   const size_t ints_bytes = off[NA] * sizeof(int32_t);
   const size_t busy_off = (ints_bytes + 255) & ~size_t(255);
   const size_t hw_off = busy_off + (((size_t)hp.P * sizeof(uint64_t) + 255) & ~size_t(255));
-  const size_t up_bytes = hw_off + (((size_t)hp.P * sizeof(uint32_t) + 255) & ~size_t(255));   // staged part ends here
+  // shared queue of the dynamic tail: [0] next position, [1] workgroups that have left, then one take count per tail item
+  const size_t queue_off = hw_off + (((size_t)hp.P * sizeof(uint32_t) + 255) & ~size_t(255));
+  const size_t up_bytes = queue_off + (((2 + hp.tail_items.size()) * sizeof(uint32_t) + 255) & ~size_t(255));   // staged part ends here
   const size_t kv_off = up_bytes;
   const size_t kv_bytes = (size_t)hp.nnz * sizeof(int32_t);
   // split-row scratch for max_batch batch entries at d = 128
@@ -162,7 +164,7 @@ int upload(dbsp_plan* plan) {
   unsigned char* st = static_cast<unsigned char*>(dv.staging);
   for (int i = 0; i < NA; ++i)
     if (!arrays[i]->empty()) std::memcpy(st + off[i] * sizeof(int32_t), arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
-  std::memset(st + busy_off, 0, up_bytes - busy_off);   // busy ticks and hardware ids start at zero
+  std::memset(st + busy_off, 0, up_bytes - busy_off);   // busy ticks, hardware ids, the queue's counters start at zero
 
   hipEvent_t ev_up, ev_use;
   DBSP_HIP(hipEventCreateWithFlags(&ev_up, hipEventDisableTiming));
@@ -183,6 +185,8 @@ int upload(dbsp_plan* plan) {
   dv.empty_rows = ints + off[4];
   dv.part_ptr = ints + off[5];
   dv.part_items = ints + off[6];
+  dv.tail_items = ints + off[7];
+  dv.queue = reinterpret_cast<uint32_t*>(dv.blob + queue_off);
   dv.kv_idx = reinterpret_cast<const int32_t*>(dv.blob + kv_off);
   dv.busy = reinterpret_cast<uint64_t*>(dv.blob + busy_off);
   dv.hw_id = reinterpret_cast<uint32_t*>(dv.blob + hw_off);
@@ -234,9 +238,14 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   dbsp_plan_opts o;
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
-  if (o.num_partitions < 0 || o.item_overhead < 0 || (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS) ||
+  if (o.num_partitions < 0 || o.item_overhead < 0 ||
+      (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS && o.mode != DBSP_MODE_REWARD) ||
       (o.flags & ~DBSP_PLAN_HOST_ONLY) || o.locality_groups < 0 || o.max_batch < 0)
     return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, groups < 0, max_batch < 0, unknown mode or flag)");
+  if (o.dynamic_tail < 0 || o.dynamic_tail >= 1000 || (o.dynamic_tail > 0 && o.mode != DBSP_MODE_ROUNDS))
+    return fail(DBSP_EINVAL, std::string(who) + ": dynamic_tail is a permille in [0, 1000) and goes with DBSP_MODE_ROUNDS only");
+  if (!(o.reward >= 0.0) || (o.reward != 0.0 && o.mode != DBSP_MODE_REWARD) || (o.mode == DBSP_MODE_REWARD && o.partition_cost))
+    return fail(DBSP_EINVAL, std::string(who) + ": reward must be >= 0, goes with DBSP_MODE_REWARD only, and that mode takes no partition_cost");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
   int32_t P = o.num_partitions;
   if (P == 0 && previous) P = previous->host.P;
@@ -263,9 +272,12 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   dbsp_plan* plan = new (std::nothrow) dbsp_plan();
   if (!plan) return fail(DBSP_ENOMEM, std::string(who) + ": out of host memory");
   std::string err;
+  dbsp_place_opts po;
+  po.P = P; po.mode = o.mode; po.max_item_len = o.max_item_len; po.item_overhead = o.item_overhead;
+  po.locality_groups = o.locality_groups; po.partition_cost = o.partition_cost;
+  po.dynamic_tail = o.dynamic_tail; po.reward = o.reward;
   if (host_only) {
-    int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups, o.partition_cost,
-                                  previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
+    int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, po, previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
     if (rc != DBSP_OK) {
       delete plan;
       return fail(rc, std::string(who) + ": " + err);
@@ -289,8 +301,7 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     hp.kv_idx = static_cast<const int32_t*>(plan->dev.staging_kv);
     dbsp_compaction job;
     dbsp_compact_begin(mask_host, hp, static_cast<int32_t*>(plan->dev.staging_kv), job);
-    rc = dbsp_plan_place(P, o.mode, o.max_item_len, o.item_overhead, o.locality_groups, o.partition_cost,
-                         previous ? &previous->host : nullptr, reuse_threshold, hp, err);
+    rc = dbsp_plan_place(po, previous ? &previous->host : nullptr, reuse_threshold, hp, err);
     const bool compacted = dbsp_compact_end(job);
     if (rc == DBSP_OK && !compacted) { rc = DBSP_ENOMEM; err = "out of host memory while planning"; }
     if (rc != DBSP_OK) {
@@ -394,6 +405,9 @@ static int forward(const dbsp_plan* plan, const void* q, const void* k, const vo
   p.empty_rows = dv.empty_rows;
   p.part_ptr = dv.part_ptr;
   p.part_items = dv.part_items;
+  p.tail_items = dv.tail_items;
+  p.queue = dv.queue;
+  p.n_tail = (int32_t)hp.tail_items.size();
   p.part_o = part_o;
   p.part_lse = part_lse;
   p.busy = dv.busy;
@@ -450,6 +464,7 @@ int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_
     case DBSP_BLOCKS_PER_HEAD: DBSP_ARR(hp.blocks_per_head);
     case DBSP_ROW_CNT: DBSP_ARR(hp.row_cnt);
     case DBSP_EMPTY_ROWS: DBSP_ARR(hp.empty_rows);
+    case DBSP_TAIL_ITEMS: DBSP_ARR(hp.tail_items);
     default: return fail(DBSP_EINVAL, "dbsp_plan_get: unknown array id");
   }
 #undef DBSP_ARR
@@ -490,6 +505,15 @@ int dbsp_plan_busy(const dbsp_plan* plan, uint64_t* busy_ticks, uint32_t* hw_id,
   DBSP_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
   if (busy_ticks) DBSP_HIP(hipMemcpy(busy_ticks, plan->dev.busy, plan->host.P * sizeof(uint64_t), hipMemcpyDeviceToHost));
   if (hw_id) DBSP_HIP(hipMemcpy(hw_id, plan->dev.hw_id, plan->host.P * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  return DBSP_OK;
+}
+
+int dbsp_plan_tail_takes(const dbsp_plan* plan, uint32_t* takes, void* stream) {
+  if (!plan || !takes) return fail(DBSP_EINVAL, "dbsp_plan_tail_takes: null pointer");
+  if (!plan->dev.resident) return fail(DBSP_EINVAL, "dbsp_plan_tail_takes: the plan was built host-only");
+  DBSP_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  const size_t n = plan->host.tail_items.size();
+  if (n) DBSP_HIP(hipMemcpy(takes, plan->dev.queue + 2, n * sizeof(uint32_t), hipMemcpyDeviceToHost));
   return DBSP_OK;
 }
 

@@ -215,11 +215,33 @@ void dbsp_fwd_kernel(
   }
 
   uint64_t busy = 0;
-  const int it_begin = g_part_ptr[part], it_end = g_part_ptr[part + 1];
-  for (int bb = 0; bb < p.B; ++bb) {
-    for (int ii = it_begin; ii < it_end; ++ii) {
+  // Work of this workgroup: its own list (once per batch entry), then items from the queue all
+  // workgroups share, taken one by one with an atomic counter -- the greedy rule "each unit to the
+  // least-loaded partition" (Methodology, "Head-level Partitioning") applied at run time, where
+  // "least loaded" is "first to run out of work".
+  __shared__ uint32_t tail_pos;
+  const int it_begin = g_part_ptr[part], n_own = g_part_ptr[part + 1] - it_begin;
+  const int64_t total_own = (int64_t)p.B * n_own;
+  const uint32_t total_tail = (uint32_t)p.B * (uint32_t)p.n_tail;
+  for (int64_t step_no = 0;; ++step_no) {
+    {
+      int it, bb;
+      if (step_no < total_own) {
+        bb = (int)(step_no / n_own);
+        it = g_part_items[it_begin + (int)(step_no % n_own)];
+      } else {
+        if (total_tail == 0) break;
+        if (t == 0) tail_pos = atomicAdd(&p.queue[0], 1u);
+        __syncthreads();
+        const uint32_t pos = __builtin_amdgcn_readfirstlane(tail_pos);
+        __syncthreads();                        // everybody has read it before the next take overwrites it
+        if (pos >= total_tail) break;
+        bb = (int)(pos / (uint32_t)p.n_tail);
+        const int tq = (int)(pos % (uint32_t)p.n_tail);
+        it = p.tail_items[tq];
+        if (t == 0) atomicAdd(&p.queue[2 + tq], 1u);     // take count, read back by dbsp_plan_tail_takes
+      }
       const uint64_t t0 = wall_clock64();
-      const int it = g_part_items[ii];
       const int4 item = g_items[it];
       const int h = item.x, I = item.y;
       const int slot = g_item_slot[it];
@@ -633,6 +655,16 @@ void dbsp_fwd_kernel(
   }
 
   if (t == 0) {
+    if (total_tail != 0) {
+      // The last workgroup to leave rewinds the queue for the next launch: by then every workgroup
+      // has made its last (failing) take.
+      __threadfence();
+      if (atomicAdd(&p.queue[1], 1u) == gridDim.x - 1) {
+        p.queue[0] = 0;
+        p.queue[1] = 0;
+        __threadfence();
+      }
+    }
     p.busy[part] = busy;
     const uint32_t hw = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);    // HW_ID
     const uint32_t xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);   // XCC_ID[3:0]

@@ -19,12 +19,14 @@ struct dbsp_fwd_params {
   const int32_t* empty_rows;
   const int32_t* part_ptr;
   const int32_t* part_items;
+  const int32_t* tail_items;  // items no partition owns, in queue order
+  uint32_t* queue;            // [0] next queue position, [1] workgroups that have left, [2 + t] times tail item t was taken
   float* part_o;       // f32 [B][n_slots][BLK][D]
   float* part_lse;     // f32 [B][n_slots][BLK]
   uint64_t* busy;      // [P]
   uint32_t* hw_id;     // [P]
   int32_t B, H, nQ, nK;
-  int32_t n_slots, n_split, n_empty;
+  int32_t n_slots, n_split, n_empty, n_tail;
   float scale;         // softmax scale
   float scale_log2;    // softmax scale * log2(e)
 };

@@ -23,7 +23,8 @@ struct dbsp_host_plan {
   std::vector<int32_t> split_rows;       // [n_split*4]
   std::vector<int32_t> empty_rows;       // [n_empty]
   std::vector<int32_t> part_ptr;         // [P+1]
-  std::vector<int32_t> part_items;       // [n_items]
+  std::vector<int32_t> part_items;       // [n_items - n_tail]
+  std::vector<int32_t> tail_items;       // [n_tail]: items no partition owns; taken from a shared queue at run time
   std::vector<int64_t> part_load;        // [P]
   std::vector<int32_t> partition_cost;   // [P] or empty (unit cost): copy of the caller's array
   int32_t n_slots = 0;
@@ -59,6 +60,8 @@ struct dbsp_device_plan {
   const int32_t* empty_rows = nullptr;
   const int32_t* part_ptr = nullptr;
   const int32_t* part_items = nullptr;
+  const int32_t* tail_items = nullptr;
+  uint32_t* queue = nullptr;      // [2 + n_tail]: next queue position, workgroups that have left, take count per tail item
   uint64_t* busy = nullptr;       // [P]
   uint32_t* hw_id = nullptr;      // [P]
   float* part_o = nullptr;        // split-row partial outputs, f32 [batches][n_slots][block][d]
@@ -84,6 +87,12 @@ struct dbsp_plan {
 // All return DBSP_OK or a negative status and fill `err`.  `prev` (may be null) is a plan of the
 // same geometry whose placement is kept if the new mask's rho_s under it does not exceed
 // `reuse_threshold`.
+struct dbsp_place_opts {
+  int32_t P = 0, mode = 0, max_item_len = 0, item_overhead = 0, locality_groups = 0;
+  const int32_t* partition_cost = nullptr;
+  int32_t dynamic_tail = 0;   // permille of the total weight left to the shared queue (round-based placement)
+  double reward = 0.0;        // R_b of DBSP_MODE_REWARD
+};
 struct dbsp_compaction {
   std::function<void(int)> body;
   void* pool = nullptr;    // set between begin and end
@@ -92,12 +101,10 @@ struct dbsp_compaction {
 int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block, dbsp_host_plan& out, std::string& err);
 void dbsp_compact_begin(const uint8_t* mask, const dbsp_host_plan& hp, int32_t* dst, dbsp_compaction& job);
 bool dbsp_compact_end(dbsp_compaction& job);
-int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                    int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
-                    double reuse_threshold, dbsp_host_plan& hp, std::string& err);
+int dbsp_plan_place(const dbsp_place_opts& opts, const dbsp_host_plan* prev, double reuse_threshold,
+                    dbsp_host_plan& hp, std::string& err);
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
-                         int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                         int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
+                         const dbsp_place_opts& opts, const dbsp_host_plan* prev,
                          double reuse_threshold, dbsp_host_plan& out, std::string& err);
 
 // rho_s of the naive and / or the greedy longest-first placement of the plan's items (each costs a placement pass).

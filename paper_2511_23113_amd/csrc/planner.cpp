@@ -268,7 +268,8 @@ void order_by_weight_desc(int64_t n_items, int64_t wmax, Weight weight, std::vec
 std::vector<int64_t> loads_of(const dbsp_host_plan& hp, const std::vector<int32_t>& assign) {
   std::vector<int64_t> ld(hp.P, 0);
   const int64_t n_items = hp.n_items();
-  for (int64_t i = 0; i < n_items; ++i) ld[assign[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
+  for (int64_t i = 0; i < n_items; ++i)
+    if (assign[i] >= 0) ld[assign[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];   // -1: left to the shared queue
   return ld;
 }
 
@@ -290,6 +291,52 @@ std::vector<int32_t> place_greedy(const dbsp_host_plan& hp) {
   order_by_weight_desc(n_items, (int64_t)hp.nK + ov, weight, order);
   LoadHeap heap(hp.P, hp.partition_cost.empty() ? nullptr : hp.partition_cost.data());
   for (int64_t t = 0; t < n_items; ++t) assign[order[t]] = heap.place(weight(order[t]));
+  return assign;
+}
+
+// Greedy longest-first placement with the paper's reward factor R_b (Methodology, "Block-level
+// Partitioning", overhead mitigation; Alg. 1, second loop) carried onto cache groups: partition p
+// belongs to group p mod G, an item's home group is q_block * G / nQ (contiguous layout), and
+// before the argmin the load of every partition of the home group is lowered by reward * weight
+// (compared in double; ties: lowest partition index).  Inside a group the offset is the same for
+// all, so the group's candidate is its least-loaded partition: one (load, index) heap per group,
+// and the argmin runs over the G heap roots.
+std::vector<int32_t> place_reward(const dbsp_host_plan& hp, int32_t G, double reward) {
+  const int64_t n_items = hp.n_items();
+  const int32_t P = hp.P, per = P / G;
+  std::vector<int32_t> assign(n_items), order;
+  const int64_t ov = hp.item_overhead;
+  auto weight = [&](int64_t i) { return (int64_t)(hp.items[4 * i + 3] - hp.items[4 * i + 2]) + ov; };
+  order_by_weight_desc(n_items, (int64_t)hp.nK + ov, weight, order);
+  std::vector<int64_t> load(P, 0);
+  std::vector<int32_t> heap((size_t)G * per);       // group g: heap[g*per ..], partition ids g, g+G, g+2G, ...
+  for (int32_t g = 0; g < G; ++g)
+    for (int32_t k = 0; k < per; ++k) heap[(size_t)g * per + k] = g + k * G;   // equal loads, ascending ids: a valid heap
+  auto less = [&](int32_t a, int32_t b) { return load[a] < load[b] || (load[a] == load[b] && a < b); };
+  for (int64_t t = 0; t < n_items; ++t) {
+    const int32_t i = order[t];
+    const int64_t w = weight(i);
+    const int32_t home = (int32_t)((int64_t)hp.items[4 * (int64_t)i + 1] * G / hp.nQ);
+    int32_t best_g = -1, best_p = -1;
+    double best_val = 0.0;
+    for (int32_t g = 0; g < G; ++g) {
+      const int32_t pt = heap[(size_t)g * per];
+      const double val = (double)load[pt] - (g == home ? reward * (double)w : 0.0);
+      if (best_g < 0 || val < best_val || (val == best_val && pt < best_p)) { best_g = g; best_p = pt; best_val = val; }
+    }
+    assign[i] = best_p;
+    load[best_p] += w;
+    int32_t* hg = heap.data() + (size_t)best_g * per;     // only the root's key grew: one sift-down
+    size_t at = 0;
+    for (;;) {
+      size_t l = 2 * at + 1, r = l + 1, m = at;
+      if (l < (size_t)per && less(hg[l], hg[m])) m = l;
+      if (r < (size_t)per && less(hg[r], hg[m])) m = r;
+      if (m == at) break;
+      std::swap(hg[at], hg[m]);
+      at = m;
+    }
+  }
   return assign;
 }
 
@@ -404,13 +451,16 @@ bool dbsp_compact_end(dbsp_compaction& job) {
   return ok;
 }
 
-int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                    int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
-                    double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
+int dbsp_plan_place(const dbsp_place_opts& opts, const dbsp_host_plan* prev, double reuse_threshold,
+                    dbsp_host_plan& hp, std::string& err) {
   try {
+    const int32_t P = opts.P, mode = opts.mode, max_item_len = opts.max_item_len, item_overhead = opts.item_overhead;
+    const int32_t locality_groups = opts.locality_groups;
+    const int32_t* partition_cost = opts.partition_cost;
     const int32_t H = hp.H, nQ = hp.nQ, nK = hp.nK;
     const int64_t R = (int64_t)H * nQ;
     hp.P = P; hp.mode = mode; hp.item_overhead = item_overhead;
+    hp.tail_items.clear();
 
     // split threshold
     int32_t L = max_item_len;
@@ -466,7 +516,7 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
     std::vector<int32_t> assign_reuse;
     if (prev && prev->H == H && prev->nQ == nQ && prev->nK == nK && prev->P == P) {
       const int64_t pn = prev->n_items();
-      std::vector<int32_t> prev_part(pn), prev_first(R + 1, 0);
+      std::vector<int32_t> prev_part(pn, -1), prev_first(R + 1, 0);   // -1: the item was in the previous plan's shared queue
       for (int32_t g = 0; g < P; ++g)
         for (int32_t k = prev->part_ptr[g]; k < prev->part_ptr[g + 1]; ++k) prev_part[prev->part_items[k]] = g;
       for (int64_t i = 0; i < pn; ++i) prev_first[(int64_t)prev->items[4 * i] * nQ + prev->items[4 * i + 1] + 1]++;
@@ -478,7 +528,7 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
         const int64_t r = (int64_t)hp.items[4 * i] * nQ + hp.items[4 * i + 1];
         chunk = (r == row_prev) ? chunk + 1 : 0;
         row_prev = r;
-        if (prev_first[r] + chunk < prev_first[r + 1]) {
+        if (prev_first[r] + chunk < prev_first[r + 1] && prev_part[prev_first[r] + chunk] >= 0) {
           assign_reuse[i] = prev_part[prev_first[r] + chunk];
           load[assign_reuse[i]] += hp.items[4 * i + 3] - hp.items[4 * i + 2];
         }
@@ -500,6 +550,7 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
     std::vector<int32_t> assign_naive, assign_lpt;
     if (!hp.reused && mode == DBSP_MODE_NAIVE) assign_naive = place_naive(hp);
     if (!hp.reused && mode == DBSP_MODE_BALANCED) assign_lpt = place_greedy(hp);
+    if (!hp.reused && mode == DBSP_MODE_REWARD) assign_lpt = place_reward(hp, locality_groups > 1 ? locality_groups : 1, opts.reward);
 
     // round-based greedy (DBSP_MODE_ROUNDS): heads in descending order of their block count
     // (the sort of Alg. 1), their items cut into consecutive rounds of P; inside a round the
@@ -518,7 +569,7 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
       seq.reserve(n_items);
       for (int32_t h : head_order)
         for (int64_t i = head_begin[h]; i < head_begin[h + 1]; ++i) seq.push_back((int32_t)i);
-      assign_rounds.assign(n_items, 0);
+      assign_rounds.assign(n_items, -1);
       // With G > 1 locality groups (partition p belongs to group p mod G: the partitions behind
       // one cache) a round is cut into G contiguous chunks of P/G items -- runs of neighbouring
       // query blocks -- and the same greedy runs one level up: heaviest chunk first, each to the
@@ -548,8 +599,24 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
           first[b] = v;
         }
       };
-      for (int64_t r0 = 0; r0 < n_items; r0 += P) {
-        const int64_t r1 = std::min<int64_t>(n_items, r0 + P);
+      // Dynamic tail: the longest suffix of the sequence whose weight is at most dynamic_tail / 1000
+      // of the total is left to a queue all partitions share (the greedy rule decided at run time,
+      // with measured finishing times as the loads); the placed part is cut back to whole rounds.
+      int64_t n_static = n_items;
+      if (opts.dynamic_tail > 0) {
+        int64_t total_w = 0;
+        for (int64_t t = 0; t < n_items; ++t) total_w += wseq[t];
+        const int64_t budget = total_w * opts.dynamic_tail / 1000;
+        int64_t tail = 0, acc = 0;
+        while (tail < n_items && acc + wseq[n_items - 1 - tail] <= budget) acc += wseq[n_items - 1 - tail++];
+        if (tail > 0) {
+          n_static = n_items - tail;
+          n_static -= n_static % P;
+        }
+      }
+      hp.tail_items.assign(seq.begin() + n_static, seq.end());
+      for (int64_t r0 = 0; r0 < n_static; r0 += P) {
+        const int64_t r1 = std::min<int64_t>(n_static, r0 + P);
         for (int32_t j = 0; j < G; ++j) {
           chunk_w[j] = 0;
           for (int64_t t = r0 + (int64_t)j * per; t < std::min<int64_t>(r1, r0 + (int64_t)(j + 1) * per); ++t) chunk_w[j] += wseq[t];
@@ -605,12 +672,14 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
     // per-partition lists: ascending item id (= ascending head, q_block, kv_begin), or, for the
     // round-based placement, the order of the rounds
     hp.part_ptr.assign(P + 1, 0);
-    for (int64_t i = 0; i < n_items; ++i) hp.part_ptr[assign[i] + 1]++;
+    for (int64_t i = 0; i < n_items; ++i)
+      if (assign[i] >= 0) hp.part_ptr[assign[i] + 1]++;
     for (int32_t g = 0; g < P; ++g) hp.part_ptr[g + 1] += hp.part_ptr[g];
-    hp.part_items.resize(n_items);
+    hp.part_items.resize(hp.part_ptr[P]);
     std::vector<int32_t> cursor(hp.part_ptr.begin(), hp.part_ptr.end() - 1);
     if (mode == DBSP_MODE_ROUNDS && !hp.reused) {
-      for (int32_t i : seq) hp.part_items[cursor[assign[i]]++] = i;
+      for (int32_t i : seq)
+        if (assign[i] >= 0) hp.part_items[cursor[assign[i]]++] = i;
     } else {
       for (int64_t i = 0; i < n_items; ++i) hp.part_items[cursor[assign[i]]++] = (int32_t)i;
     }
@@ -622,8 +691,7 @@ int dbsp_plan_place(int32_t P, int32_t mode, int32_t max_item_len, int32_t item_
 }
 
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
-                         int32_t P, int32_t mode, int32_t max_item_len, int32_t item_overhead,
-                         int32_t locality_groups, const int32_t* partition_cost, const dbsp_host_plan* prev,
+                         const dbsp_place_opts& opts, const dbsp_host_plan* prev,
                          double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
   int rc = dbsp_plan_count(mask, H, nQ, nK, block, hp, err);
   if (rc != DBSP_OK) return rc;
@@ -636,7 +704,7 @@ int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK,
   hp.kv_idx = hp.kv_store.data();
   dbsp_compaction job;
   dbsp_compact_begin(mask, hp, hp.kv_store.data(), job);     // runs beside the placement
-  rc = dbsp_plan_place(P, mode, max_item_len, item_overhead, locality_groups, partition_cost, prev, reuse_threshold, hp, err);
+  rc = dbsp_plan_place(opts, prev, reuse_threshold, hp, err);
   const bool ok = dbsp_compact_end(job);
   if (rc == DBSP_OK && !ok) { err = "out of host memory while planning"; rc = DBSP_ENOMEM; }
   return rc;

@@ -9,6 +9,7 @@ from .tensors import bf16_bits_to_f32, f32_to_bf16_bits, normal_bf16, qkv_for_co
 from .masks import (  # noqa: F401
     CONFIGS,
     config_shape,
+    imbalance_sweep_mask,
     mask_for_config,
     mask_sequence_cfg5,
     random_mask,

@@ -170,3 +170,26 @@ def random_mask(H: int, nQ: int, nK: int, density: float, seed: int, keep_diag: 
         k = min(nQ, nK)
         m[:, np.arange(k), np.arange(k)] = 1
     return m
+
+
+def imbalance_sweep_mask(rho_target: float, seed: int = 0) -> np.ndarray:
+    """A mask of config 3's shape (40 heads, 256 x 256 blocks, mean density 0.3) whose per-head
+    densities are spread so that a contiguous row-major split over 256 partitions has an
+    imbalance ratio of about rho_target (between 1 and 3): a quarter of the heads get density
+    0.3 * rho_target, the others share the rest evenly; inside a head the diagonal is on and the
+    other blocks are uniformly random to the head's count.  (Stands in for the synthetic masks of
+    the paper's speed-up-against-imbalance experiment, whose recipe the paper does not give.)"""
+    c = CONFIGS[3]
+    H, n = c["H"], c["nQ"]
+    heavy = H // 4
+    d_hi = min(0.95, 0.3 * float(rho_target))
+    d_lo = max(0.01, (0.3 * H - d_hi * heavy) / (H - heavy))
+    ss = np.random.SeedSequence([9100, int(seed), int(round(rho_target * 1000))]).spawn(H + 1)
+    order = np.random.Generator(np.random.PCG64(ss[H])).permutation(H)       # which heads are the heavy ones
+    mask = np.zeros((H, n, n), dtype=np.uint8)
+    for k, h in enumerate(order):
+        rng = np.random.Generator(np.random.PCG64(ss[h]))
+        m = mask[h]
+        m[np.arange(n), np.arange(n)] = 1
+        _fill_to_count(m, int(round((d_hi if k < heavy else d_lo) * n * n)), rng)
+    return mask

@@ -91,10 +91,11 @@ def test_imbalance_ratio_matches_oracle_and_hand_values():
         assert B.imbalance_ratio(w) == op.imbalance_ratio(w.tolist())
 
 
-def _assert_plan_equal(mask, block, P, mode, L, c0, G=0, cost=None):
+def _assert_plan_equal(mask, block, P, mode, L, c0, G=0, cost=None, tail=0, reward=0.0):
     pl = B.plan_sparse_attn(mask, block, num_partitions=P, mode=mode, max_item_len=L, item_overhead=c0, host_only=True,
-                            locality_groups=G, partition_cost=cost)
-    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0, locality_groups=G, partition_cost=cost)
+                            locality_groups=G, partition_cost=cost, dynamic_tail=tail, reward=reward)
+    ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0, locality_groups=G, partition_cost=cost,
+                  dynamic_tail=tail, reward=reward)
     st = pl.stats()
     assert st["nnz"] == ref["nnz"] and st["n_items"] == len(ref["items"])
     assert st["num_partitions"] == P and st["max_item_len"] == ref["max_item_len"]
@@ -111,6 +112,7 @@ def _assert_plan_equal(mask, block, P, mode, L, c0, G=0, cost=None):
     eq(pl.array(B.PART_PTR), np.array(ref["part_ptr"], dtype=np.int32))
     eq(pl.array(B.PART_ITEMS), np.array(ref["part_items"], dtype=np.int32))
     eq(pl.array(B.PART_LOAD), np.array(ref["part_load"], dtype=np.int64))
+    eq(pl.array(B.TAIL_ITEMS), np.array(ref["tail_items"], dtype=np.int32))
     empty = [r for r, c in enumerate(ref["cnt"]) if c == 0]
     eq(pl.array(B.EMPTY_ROWS), np.array(empty, dtype=np.int32))
     pl.close()
@@ -356,3 +358,58 @@ def test_rho_of_the_unused_placements_is_worked_out_on_request():
     assert full["rho_naive"] == ref["rho_naive"] and full["rho_balanced"] == ref["rho_balanced"] and full["rho_plan"] == ref["rho_plan"]
     assert p.stats() == full                      # the second call reads the stored values
     p.close()
+
+
+def test_dynamic_tail_bit_exact_and_errors():
+    for cfg, P in ((3, 256), (5, 256), (2, 1024), (1, 8)):
+        mask = synth.mask_for_config(cfg)
+        block = synth.CONFIGS[cfg]["block"]
+        for tail, G in ((30, 8), (100, 1), (999, 4)):
+            _assert_plan_equal(mask, block, P, B.MODE_ROUNDS, 0, 0, G, None, tail)
+    rng = np.random.default_rng(5)
+    for seed in range(12):
+        H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0, 1)), seed=seed)
+        P = int(rng.choice([1, 2, 4, 6]))
+        cost = rng.integers(1, 50, P).tolist() if seed % 3 == 0 else None
+        _assert_plan_equal(mask, 64, P, B.MODE_ROUNDS, int(rng.choice([0, 2, -1])), int(rng.integers(0, 3)), 1, cost, int(rng.integers(1, 600)))
+    # a plan with a queue as the previous plan of a reuse chain: queued items count as new ones
+    seq = list(synth.mask_sequence_cfg5(3))
+    prev = B.plan_sparse_attn(seq[0], 128, num_partitions=256, mode=B.MODE_ROUNDS, host_only=True, dynamic_tail=100)
+    ref_prev = op.plan(seq[0], 256, mode=op.MODE_ROUNDS, dynamic_tail=100)
+    assert len(ref_prev["tail_items"]) > 0
+    nxt, reused, rho = B.plan_sparse_attn_reuse(prev, seq[1], 1.5, mode=B.MODE_ROUNDS, host_only=True)
+    ref = op.plan(seq[1], 256, mode=op.MODE_ROUNDS, previous=ref_prev, reuse_threshold=1.5)
+    assert reused == ref["reused"] and rho == ref["rho_reuse"] and nxt.array(B.PART_ITEMS).tolist() == ref["part_items"]
+    assert nxt.array(B.TAIL_ITEMS).shape == (0,) or not reused
+    prev.close()
+    nxt.close()
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    mp = m.ctypes.data_as(C.c_void_p)
+    for mode, tail in ((B.MODE_ROUNDS, 1000), (B.MODE_ROUNDS, -1), (B.MODE_BALANCED, 10)):
+        assert _plan_raw(mp, 1, 2, 2, 64, B.PlanOpts(4, mode, 0, 0, B.PLAN_HOST_ONLY, 0, None, 0, tail, 0.0))[0] == B.DBSP_EINVAL
+
+
+def test_reward_mode_bit_exact_and_errors():
+    for cfg, P in ((3, 256), (5, 256), (1, 8)):
+        mask = synth.mask_for_config(cfg)
+        block = synth.CONFIGS[cfg]["block"]
+        for G, rb in ((8, 0.0), (8, 0.5), (8, 2.0), (1, 1.0), (4, 1e6)):
+            if P % G == 0:
+                _assert_plan_equal(mask, block, P, B.MODE_REWARD, 0, 0, G, None, 0, rb)
+    rng = np.random.default_rng(6)
+    for seed in range(12):
+        H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0, 1)), seed=seed)
+        P, G = [(4, 2), (6, 3), (5, 1), (8, 4)][seed % 4]
+        _assert_plan_equal(mask, 64, P, B.MODE_REWARD, int(rng.choice([0, 2, -1])), int(rng.integers(0, 3)), G, None, 0, float(rng.choice([0.0, 0.3, 1.0, 2.5])))
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    mp = m.ctypes.data_as(C.c_void_p)
+    cost = (C.c_int32 * 4)(1, 1, 1, 1)
+    bad = (B.PlanOpts(4, B.MODE_REWARD, 0, 0, B.PLAN_HOST_ONLY, 2, None, 0, 0, -1.0),
+           B.PlanOpts(4, B.MODE_REWARD, 0, 0, B.PLAN_HOST_ONLY, 2, None, 0, 0, float("nan")),
+           B.PlanOpts(4, B.MODE_BALANCED, 0, 0, B.PLAN_HOST_ONLY, 2, None, 0, 0, 1.0),
+           B.PlanOpts(4, B.MODE_REWARD, 0, 0, B.PLAN_HOST_ONLY, 2, C.cast(cost, C.c_void_p), 0, 0, 1.0),
+           B.PlanOpts(4, B.MODE_REWARD, 0, 0, B.PLAN_HOST_ONLY, 3, None, 0, 0, 1.0))
+    for o in bad:
+        assert _plan_raw(mp, 1, 2, 2, 64, o)[0] == B.DBSP_EINVAL

@@ -140,14 +140,16 @@ def _sample_rows(mask, per_head, seed):
 @pytest.mark.parametrize("cfg,per_head", [(2, 2), (3, 2), (5, 4), (4, 2)])
 def test_full_size_configs_sampled_rows(cfg, per_head):
     # the launch configuration the benchmark times: default partitions, round-based placement with
-    # one locality group per XCD
+    # one locality group per XCD, 40 permille of the work in the shared queue
     c = synth.config_shape(cfg)
     block, d = c["block"], c["d"]
     mask = synth.mask_for_config(cfg)
     qb, kb, vb = synth.qkv_for_config(cfg, c["B"], c["H"], c["Nq"], c["Nk"], d)
-    plan, O, L = _run(mask, block, qb, kb, vb, mode=op.MODE_ROUNDS, locality_groups=8)
-    ref = op.plan(mask, plan.stats()["num_partitions"], mode=op.MODE_ROUNDS, locality_groups=8)
+    plan, O, L = _run(mask, block, qb, kb, vb, mode=op.MODE_ROUNDS, locality_groups=8, dynamic_tail=40)
+    ref = op.plan(mask, plan.stats()["num_partitions"], mode=op.MODE_ROUNDS, locality_groups=8, dynamic_tail=40)
     rows = _sample_rows(mask, per_head, seed=cfg)
+    for i in ref["tail_items"][:2] + ref["tail_items"][-2:]:          # rows that are taken from the queue
+        rows.append((0, ref["items"][i][0], ref["items"][i][1]))
     # every split row's chunks sit in different partitions: add some split rows and their neighbours
     for r, _, _ in ref["split_rows"][:6]:
         h, I = divmod(r, c["nQ"])
@@ -172,6 +174,7 @@ def test_full_size_configs_sampled_rows(cfg, per_head):
     assert st["rho_balanced"] == ref["rho_balanced"] and st["rho_plan"] == ref["rho_plan"] and st["nnz"] == ref["nnz"]
     busy, hw = plan.busy()
     assert busy.shape == (st["num_partitions"],) and (busy > 0).sum() >= min(st["num_partitions"], st["n_items"]) * 0.99
+    assert plan.tail_takes().tolist() == [1] * len(ref["tail_items"])          # every queued item taken exactly once
     plan.close()
 
 
@@ -186,7 +189,7 @@ def test_config5_all_rows_in_the_benchmark_placement_and_the_greedy_one():
     q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
     Or, Lr = oa.masked_attention(q32, k32, v32, mask, block, dtype=np.float32)
     assert np.isfinite(Lr).all()
-    for kw in (dict(mode=op.MODE_ROUNDS, locality_groups=8), dict(mode=op.MODE_BALANCED)):
+    for kw in (dict(mode=op.MODE_ROUNDS, locality_groups=8, dynamic_tail=40), dict(mode=op.MODE_BALANCED)):
         plan, O, L = _run(mask, block, qb, kb, vb, **kw)
         st = plan.stats()
         assert st["n_items"] > c["H"] * c["nQ"]              # some rows are split
@@ -372,6 +375,70 @@ def test_scores_that_keep_growing_take_the_rescale_path(block, d):
         # scores reach a few hundred here: O stays a convex combination of V rows, LSE is large
         _check_all_rows(mask, block, qb, kb, vb, O, L)
         plan.close()
+
+
+def test_dynamic_tail_takes_every_queued_item_exactly_once():
+    # part of the items sits in a queue all workgroups share; whoever runs out of placed work takes the
+    # next one.  Coverage: after n launches with batch size B every queued item was taken n * B times;
+    # results are those of the fully placed plan bit for bit (who computes an item does not matter)
+    import torch
+    import paper_2511_23113_amd as dbsp
+    from paper_2511_23113_amd import binding as B
+    c = synth.config_shape(5)
+    block, d = c["block"], c["d"]
+    mask = synth.mask_for_config(5)
+    qb, kb, vb = synth.qkv_for_config(5, 2, c["H"], c["Nq"], c["Nk"], d)
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    static = dbsp.plan_sparse_attn(mask, block, mode=dbsp.MODE_ROUNDS, locality_groups=8, max_batch=2)
+    o_ref, l_ref = dbsp.sparse_attn_fwd(static, q, k, v)
+    queued = dbsp.plan_sparse_attn(mask, block, mode=dbsp.MODE_ROUNDS, locality_groups=8, max_batch=2, dynamic_tail=150)
+    ref = op.plan(mask, 256, mode=op.MODE_ROUNDS, locality_groups=8, dynamic_tail=150)
+    n_tail = len(ref["tail_items"])
+    assert n_tail > 100 and queued.array(B.TAIL_ITEMS).tolist() == ref["tail_items"]
+    assert sorted(queued.array(B.PART_ITEMS).tolist() + ref["tail_items"]) == list(range(len(ref["items"])))
+    for launch in range(1, 4):
+        o = torch.full_like(q, float("nan"))
+        lse = torch.full((2, c["H"], c["Nq"]), float("nan"), dtype=torch.float32, device="cuda")
+        dbsp.sparse_attn_fwd(queued, q, k, v, o=o, lse=lse)
+        assert queued.tail_takes().tolist() == [2 * launch] * n_tail
+        assert torch.equal(o, o_ref) and torch.equal(lse, l_ref)
+    busy, _ = queued.busy()
+    assert (busy > 0).all()
+    rows = [(b, ref["items"][i][0], ref["items"][i][1]) for b in (0, 1) for i in ref["tail_items"][:2] + ref["tail_items"][-2:]]
+    q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    Or, Lr = oa.masked_attention_rows(q32, k32, v32, mask, block, rows)
+    O = _host_f32(o).reshape(2, c["H"], c["nQ"], block, d)
+    L = lse.cpu().numpy().reshape(2, c["H"], c["nQ"], block)
+    for t, (b, h, I) in enumerate(rows):
+        assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL and np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL
+    static.close()
+    queued.close()
+    # everything queued (one partition's worth of rounds is never reached): small shape, 64-token blocks
+    small = synth.random_mask(2, 5, 7, 0.6, seed=8, keep_diag=True)
+    qs, ks, vs = synth.normal_bf16((1, 2, 5 * 64, 64), 51), synth.normal_bf16((1, 2, 7 * 64, 64), 52), synth.normal_bf16((1, 2, 7 * 64, 64), 53)
+    plan, O, L = _run(small, 64, qs, ks, vs, mode=op.MODE_ROUNDS, num_partitions=16, dynamic_tail=999)
+    assert len(plan.array(B.PART_ITEMS)) == 0 and plan.tail_takes().tolist() == [1] * len(plan.array(B.TAIL_ITEMS))
+    _check_all_rows(small, 64, qs, ks, vs, O, L)
+    plan.close()
+
+
+def test_reward_mode_matches_the_oracle():
+    c = synth.config_shape(5)
+    mask = synth.mask_for_config(5)
+    qb, kb, vb = synth.qkv_for_config(5, c["B"], c["H"], c["Nq"], c["Nk"], c["d"])
+    plan, O, L = _run(mask, c["block"], qb, kb, vb, mode=op.MODE_REWARD, locality_groups=8, reward=1.0)
+    ref = op.plan(mask, 256, mode=op.MODE_REWARD, locality_groups=8, reward=1.0)
+    from paper_2511_23113_amd import binding as B
+    assert plan.array(B.PART_ITEMS).tolist() == ref["part_items"] and plan.stats()["rho_plan"] == ref["rho_plan"]
+    rows = [(0, h, I) for h, I in ((0, 0), (3, 17), (9, 127), (5, 64))] + [(0, r // c["nQ"], r % c["nQ"]) for r, _, _ in ref["split_rows"][:2]]
+    q32, k32, v32 = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    Or, Lr = oa.masked_attention_rows(q32, k32, v32, mask, c["block"], rows)
+    O = O.reshape(c["B"], c["H"], c["nQ"], c["block"], c["d"])
+    L = L.reshape(c["B"], c["H"], c["nQ"], c["block"])
+    for t, (b, h, I) in enumerate(rows):
+        assert np.abs(O[b, h, I] - Or[t]).max() <= O_TOL and np.abs(L[b, h, I] - Lr[t]).max() <= LSE_TOL
+    assert np.isfinite(O).all() and np.isfinite(L).all()
+    plan.close()
 
 
 def test_batch_beyond_the_plans_max_batch_is_refused():

@@ -371,3 +371,57 @@ def test_calibration_by_hand_and_its_effect():
     slow = [tuned["part_load"][g] for g in range(256) if g % 8 == 7]
     fast = [tuned["part_load"][g] for g in range(256) if g % 8 != 7]
     assert 0.93 < (sum(slow) / len(slow)) / (sum(fast) / len(fast)) < 0.97
+
+
+def test_dynamic_tail_by_hand():
+    # rows of head 0: 5, 4, 3 blocks (and an empty one); of head 1: 2, 1, 1, 1; two partitions, no splits.
+    # Heads in descending order of their count (12, 5): sequence = items 0..6, total weight 17.
+    mask = np.zeros((2, 4, 5), dtype=np.uint8)
+    for (h, I), c in {(0, 0): 5, (0, 1): 4, (0, 2): 3, (1, 0): 2, (1, 1): 1, (1, 2): 1, (1, 3): 1}.items():
+        mask[h, I, :c] = 1
+    # 250 permille: budget 17 * 250 // 1000 = 4: from the end 1 + 1 + 1 fit, the 2 does not: three items queue,
+    # four are placed (two whole rounds): round {5, 4} -> p0, p1; round {3, 2}: 3 -> p1 (4), 2 -> p0 (5)
+    r = op.plan(mask, 2, mode=op.MODE_ROUNDS, max_item_len=-1, dynamic_tail=250)
+    assert r["tail_items"] == [4, 5, 6] and r["part_items"] == [0, 3, 1, 2] and r["part_ptr"] == [0, 2, 4]
+    assert r["part_load"] == [7, 7] and r["rho_plan"] == 1.0
+    # 300 permille: budget 5: 1 + 1 + 1 + 2 fit; three items are left, cut back to one whole round of two
+    r = op.plan(mask, 2, mode=op.MODE_ROUNDS, max_item_len=-1, dynamic_tail=300)
+    assert r["tail_items"] == [2, 3, 4, 5, 6] and r["part_items"] == [0, 1] and r["part_load"] == [5, 4]
+    # nothing fits the budget: everything is placed, as without the option
+    r0 = op.plan(mask, 2, mode=op.MODE_ROUNDS, max_item_len=-1)
+    r1 = op.plan(mask, 2, mode=op.MODE_ROUNDS, max_item_len=-1, dynamic_tail=50)
+    assert r1["tail_items"] == [] and r1["part_items"] == r0["part_items"]
+    # every item is in exactly one place
+    for t in (250, 300, 999):
+        r = op.plan(mask, 2, mode=op.MODE_ROUNDS, max_item_len=-1, dynamic_tail=t)
+        assert sorted(r["part_items"] + r["tail_items"]) == list(range(7))
+
+
+def test_reward_placement_by_hand():
+    # four partitions in two groups (p0, p2 | p1, p3); four query blocks: blocks 0, 1 are at home in group 0, 2, 3 in group 1
+    w, q = [5, 5, 4, 3, 3], [0, 0, 1, 3, 1]
+    # no reward: the plain greedy: 5 -> p0, 5 -> p1, 4 -> p2, 3 -> p3, 3 -> p3 (least loaded)
+    assert op.reward_partition(q, w, 4, 4, 2, 0.0) == [0, 1, 2, 3, 3] == op.lpt_partition(w, 4)[0]
+    # R_b = 1: 5 -> p0 [-5, 0, -5, 0]; 5 -> p2 [0, 0, -5, 0]; 4 (home 0) -> p1 [1, 0, 1, 0]; 3 (home 1) -> p3 [5, 1, 5, -3];
+    # 3 (home 0) -> p0 [2, 4, 2, 3]
+    assert op.reward_partition(q, w, 4, 4, 2, 1.0) == [0, 2, 1, 3, 0]
+    # R_b = 0.5: ... the last 3 (home 0) sees [3.5, 4, 3.5, 3] and leaves its home group for p3
+    assert op.reward_partition(q, w, 4, 4, 2, 0.5) == [0, 2, 1, 3, 3]
+    # a very large reward keeps every item inside its home group, balanced there by the same greedy
+    rng = np.random.default_rng(3)
+    for _ in range(30):
+        n, nQ = int(rng.integers(1, 40)), 12
+        ww, qq = rng.integers(1, 30, n).tolist(), rng.integers(0, nQ, n).tolist()
+        a = op.reward_partition(qq, ww, nQ, 6, 3, 1e9)
+        assert all(p % 3 == qq[i] * 3 // nQ for i, p in enumerate(a))
+        for g in range(3):
+            mine = [i for i in range(n) if qq[i] * 3 // nQ == g]
+            inner, _ = op.lpt_partition([ww[i] for i in mine], 2)
+            assert [a[i] for i in mine] == [g + 3 * k for k in inner]
+    # through plan(): lists in ascending item order, every item placed once
+    mask = synth.random_mask(3, 8, 10, 0.5, seed=9, keep_diag=True)
+    r = op.plan(mask, 4, mode=op.MODE_REWARD, locality_groups=2, reward=0.7)
+    assert sorted(r["part_items"]) == list(range(len(r["items"]))) and r["tail_items"] == []
+    for g in range(4):
+        lst = r["part_items"][r["part_ptr"][g]:r["part_ptr"][g + 1]]
+        assert lst == sorted(lst)
