@@ -115,7 +115,7 @@ def low_density_heads(dbsp, torch, np, c, mask, q, k, v, o, lse, plan_kw):
     m2 = mask.copy()
     m2[[h for h in range(mask.shape[0]) if h not in set(low.tolist())]] = 0
     plan = dbsp.plan_sparse_attn(m2, block, **plan_kw)
-    ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=5)
+    ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=10, warm=5)
     plan.close()
     pairs = int((m2 != 0).sum())
     return {"heads": low.tolist(), "density": [round(float(x), 4) for x in dens[low]], "active_blocks": pairs,
@@ -140,7 +140,8 @@ def other_config(dbsp, synth, torch, np, cfg, plan_kw):
         plan_ms.append(plan.stats(with_rho=False)["plan_usec"] / 1e3)
         if _ < 3:
             plan.close()
-    ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=5 if cfg != 4 else 3)
+    # short kernels: enough warm-up launches for the clocks to come back up after the host-side set-up
+    ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=10 if cfg != 4 else 3, warm=10 if cfg != 4 else 2)
     rho_busy, _ = busy_rho_per_cu(np, plan)
     st = plan.stats()
     plan.close()

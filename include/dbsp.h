@@ -47,7 +47,9 @@ enum { DBSP_PLAN_HOST_ONLY = 1 }; /* flags bit: build the plan on the host only 
 
 typedef struct dbsp_plan_opts {
   int32_t num_partitions; /* P >= 1; 0 -> number of compute units of the current device (256 when no device),
-                             times 4 when block <= 64 (those workgroups are two waves each) */
+                             times 4 when block <= 64 (those workgroups are two waves each: four fill a compute
+                             unit at d = 64; at d = 128 their tiles leave room for two at a time and the other
+                             half of the workgroups follow as the first finish, which the even split allows) */
   int32_t mode;           /* DBSP_MODE_BALANCED: greedy longest-first placement (Alg. 1, first loop);
                              DBSP_MODE_NAIVE: items in row-major order dealt in contiguous runs of
                              ceil(n_items / P) -- the unbalanced baseline rho_s is quoted against;

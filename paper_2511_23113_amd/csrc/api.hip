@@ -259,7 +259,8 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
       else
         (void)hipGetLastError();
     }
-    // a 64-token block is served by a two-wave workgroup: four of them fill a compute unit
+    // a 64-token block is served by a two-wave workgroup: four of them fill a compute unit at d = 64
+    // (at d = 128 two are resident at a time; the plan does not know d, and an even split runs in two rounds)
     if (block <= 64) P *= 4;
   }
   if (previous && (previous->host.H != H || previous->host.nQ != nQ || previous->host.nK != nK || previous->host.P != P))
