@@ -676,48 +676,45 @@ void dbsp_fwd_kernel(
 // Fix-up pass: merges the chunks of split rows (log-sum-exp identity, the same one that
 // combines per-chunk partial attention in Ring Attention) and fills rows with no active block.
 //   LSE = log sum_k exp(LSE_k),  O = sum_k exp(LSE_k - LSE) O_k;   empty row: O = 0, LSE = -inf.
-// Grid: B * (n_split + n_empty) workgroups of 256 threads.
+// Grid: (B * (n_split + n_empty), blk * D / 4 / 256) workgroups of 256 threads; a thread produces four
+// consecutive d-values of one query (all its loads are independent of each other: the pass is
+// bandwidth-bound, not latency-bound).
 template <int D>
 __global__ __launch_bounds__(256) void dbsp_fixup_kernel(const dbsp_fwd_params p, int blk) {
   const int per_b = p.n_split + p.n_empty;
   const int bb = blockIdx.x / per_b, e = blockIdx.x % per_b;
-  const int n4 = blk * (D / 4);
+  const int x = blockIdx.y * 256 + threadIdx.x;          // < blk * D / 4
+  const int qloc = x / (D / 4), d4 = x % (D / 4);
   if (e < p.n_split) {
     const int4 sr = reinterpret_cast<const int4*>(p.split_rows)[e];
     const int row = sr.x, first = sr.y, nch = sr.z;
     const int h = row / p.nQ, I = row % p.nQ;
     const int64_t bh = (int64_t)bb * p.H + h;
     const int64_t ps0 = (int64_t)bb * p.n_slots + first;
-    for (int x = threadIdx.x; x < n4; x += 256) {
-      const int qloc = x / (D / 4), d4 = x % (D / 4);
-      float mx = -INFINITY;
-      for (int kx = 0; kx < nch; ++kx) mx = fmaxf(mx, p.part_lse[(ps0 + kx) * blk + qloc]);
-      float tot = 0.f;
-      for (int kx = 0; kx < nch; ++kx) tot += __expf(p.part_lse[(ps0 + kx) * blk + qloc] - mx);
-      const float lse = mx + __logf(tot);
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      for (int kx = 0; kx < nch; ++kx) {
-        const float wgt = __expf(p.part_lse[(ps0 + kx) * blk + qloc] - lse);
-        const f32x4 f = *reinterpret_cast<const f32x4*>(p.part_o + ((ps0 + kx) * blk + qloc) * D + 4 * d4);
-        acc.x += wgt * f.x;  acc.y += wgt * f.y;  acc.z += wgt * f.z;  acc.w += wgt * f.w;
-      }
-      const int64_t tok = bh * p.nQ * blk + (int64_t)I * blk + qloc;
-      u32x2 pk;
-      pk.x = pack_bf16x2(acc.x, acc.y);
-      pk.y = pack_bf16x2(acc.z, acc.w);
-      *reinterpret_cast<u32x2*>(p.o + tok * D + 4 * d4) = pk;
-      if (p.lse != nullptr && d4 == 0) p.lse[tok] = lse;
+    float mx = -INFINITY;
+    for (int kx = 0; kx < nch; ++kx) mx = fmaxf(mx, p.part_lse[(ps0 + kx) * blk + qloc]);
+    float tot = 0.f;
+    for (int kx = 0; kx < nch; ++kx) tot += __expf(p.part_lse[(ps0 + kx) * blk + qloc] - mx);
+    const float lse = mx + __logf(tot);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int kx = 0; kx < nch; ++kx) {
+      const float wgt = __expf(p.part_lse[(ps0 + kx) * blk + qloc] - lse);
+      const f32x4 f = *reinterpret_cast<const f32x4*>(p.part_o + ((ps0 + kx) * blk + qloc) * D + 4 * d4);
+      acc.x += wgt * f.x;  acc.y += wgt * f.y;  acc.z += wgt * f.z;  acc.w += wgt * f.w;
     }
+    const int64_t tok = bh * p.nQ * blk + (int64_t)I * blk + qloc;
+    u32x2 pk;
+    pk.x = pack_bf16x2(acc.x, acc.y);
+    pk.y = pack_bf16x2(acc.z, acc.w);
+    *reinterpret_cast<u32x2*>(p.o + tok * D + 4 * d4) = pk;
+    if (p.lse != nullptr && d4 == 0) p.lse[tok] = lse;
   } else {
     const int row = p.empty_rows[e - p.n_split];
     const int h = row / p.nQ, I = row % p.nQ;
     const int64_t bh = (int64_t)bb * p.H + h;
-    for (int x = threadIdx.x; x < n4; x += 256) {
-      const int qloc = x / (D / 4), d4 = x % (D / 4);
-      const int64_t tok = bh * p.nQ * blk + (int64_t)I * blk + qloc;
-      *reinterpret_cast<u32x2*>(p.o + tok * D + 4 * d4) = u32x2{0u, 0u};
-      if (p.lse != nullptr && d4 == 0) p.lse[tok] = -INFINITY;
-    }
+    const int64_t tok = bh * p.nQ * blk + (int64_t)I * blk + qloc;
+    *reinterpret_cast<u32x2*>(p.o + tok * D + 4 * d4) = u32x2{0u, 0u};
+    if (p.lse != nullptr && d4 == 0) p.lse[tok] = -INFINITY;
   }
 }
 
@@ -754,8 +751,9 @@ hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, int P, hi
   if (e != hipSuccess) return e;
   const int fix = p.B * (p.n_split + p.n_empty);
   if (fix > 0) {
-    if (d == 128) hipLaunchKernelGGL((dbsp_fixup_kernel<128>), dim3(fix), dim3(256), 0, stream, p, block);
-    else hipLaunchKernelGGL((dbsp_fixup_kernel<64>), dim3(fix), dim3(256), 0, stream, p, block);
+    const dim3 grid(fix, block * d / 4 / 256);      // block >= 64 and d >= 64: a whole number of workgroups per row
+    if (d == 128) hipLaunchKernelGGL((dbsp_fixup_kernel<128>), grid, dim3(256), 0, stream, p, block);
+    else hipLaunchKernelGGL((dbsp_fixup_kernel<64>), grid, dim3(256), 0, stream, p, block);
     e = hipGetLastError();
   }
   return e;
