@@ -123,6 +123,31 @@ def low_density_heads(dbsp, torch, np, c, mask, q, k, v, o, lse, plan_kw):
             "tflops": pairs * 4.0 * block * block * d / (ms * 1e-3) / 1e12}
 
 
+def pair_rows(dbsp, synth, torch, np, c, mask, q, k, v, o, lse, plan_kw, keeps=(1.0, 0.75, 0.5)):
+    """64-token mask blocks at d = 128 (the paper's PAROAttention block size: Methodology, "Block-level
+    Partitioning") on the workload's tensors: its mask refined to half blocks, served by the plain
+    two-wave kernel and by 128-query workgroups over pair rows (extra launches).  flag_fill = share of
+    the (query block, KV block) combinations of the super blocks that the mask has."""
+    rows = []
+    for keep in keeps:
+        fine = synth.refine_to_half_blocks(mask, keep)
+        nnz = int(fine.sum())
+        flops = float(c["B"]) * nnz * 4.0 * 64 * 64 * c["d"]
+        row = {"keep": keep, "active_blocks": nnz}
+        for name, pair in (("plain", False), ("pair_rows", True)):
+            plan = dbsp.plan_sparse_attn(fine, 64, **dict(plan_kw, num_partitions=0, partition_cost=None, pair_rows=pair))
+            ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=5, warm=3)
+            rho_busy, _ = busy_rho_per_cu(np, plan)
+            st = plan.stats(with_rho=False)
+            row[name] = {"kernel_ms": ms, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                         "partitions": st["num_partitions"], "plan_ms": st["plan_usec"] / 1e3, "rho_busy_per_cu": rho_busy}
+            if pair:
+                row[name]["flag_fill"] = nnz / (4.0 * st["nnz"])
+            plan.close()
+        rows.append(row)
+    return rows
+
+
 def other_config(dbsp, synth, torch, np, cfg, plan_kw):
     """One of the other workload configs under the same placement options: kernel time, fraction of the
     bf16 MFMA peak, algorithmic bytes per second, planning time, busy-time imbalance (extra launches)."""
@@ -476,6 +501,8 @@ def main():
         ld = low_density_heads(dbsp, torch, np, c, mask, q, k, v, o, lse, kw_timed)
         if ld is not None:
             out["low_density_heads"] = ld
+        if block == 128 and d == 128:
+            out["half_blocks_64_tokens"] = pair_rows(dbsp, synth, torch, np, c, mask, q, k, v, o, lse, kw_timed)
     if args.speedup_sweep and cfg == 3:
         out["speedup_vs_imbalance"] = speedup_sweep(dbsp, synth, torch, np, q, k, v, o, lse, kw_timed)
     if args.placement_sweep:

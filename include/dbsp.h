@@ -42,14 +42,28 @@ typedef enum dbsp_status {
 typedef struct dbsp_plan dbsp_plan;
 
 enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1, DBSP_MODE_ROUNDS = 2, DBSP_MODE_REWARD = 3 };
-enum { DBSP_PLAN_HOST_ONLY = 1 }; /* flags bit: build the plan on the host only (no device, no upload);
-                                     such a plan cannot be passed to sparse_attn_fwd */
+enum {
+  DBSP_PLAN_HOST_ONLY = 1, /* flags bit: build the plan on the host only (no device, no upload);
+                              such a plan cannot be passed to sparse_attn_fwd */
+  DBSP_PLAN_PAIR_ROWS = 2  /* flags bit, block == 64 only, forward pass at d == 128 only: 64-token blocks (the block
+                              size of the paper's PAROAttention masks: Methodology, "Block-level Partitioning") served
+                              by 128-query workgroups.  A row of the plan is then a pair of neighbouring query blocks
+                              (2p, 2p+1) of a head and its KV list the ascending union of the two rows' lists, cut into
+                              consecutive pairs ("super blocks", the unit of work and of every count, length and rho_s
+                              of such a plan); the (query block, KV block) combinations of a super block that the
+                              mask does not have are computed with the rest and given probability zero, so K and V
+                              must be finite in every block that either row of a pair uses.  DBSP_ROW_CNT / ROW_PTR / ITEMS then refer to pair rows (ceil(nQ / 2) per head) and
+                              super blocks, and DBSP_KV_IDX holds two int32 per super block: j0, and j1 | flags << 24
+                              with flags bit (q + 2k) = "query block 2p+q needs KV block j_k" (a union of odd length
+                              ends with j1 = j0 and no flag for the second slot) */
+};
 
 typedef struct dbsp_plan_opts {
   int32_t num_partitions; /* P >= 1; 0 -> number of compute units of the current device (256 when no device),
-                             times 4 when block <= 64 (those workgroups are two waves each: four fill a compute
-                             unit at d = 64; at d = 128 their tiles leave room for two at a time and the other
-                             half of the workgroups follow as the first finish, which the even split allows) */
+                             times 4 when block <= 64 without DBSP_PLAN_PAIR_ROWS (those workgroups are two
+                             waves each: four fill a compute unit at d = 64; at d = 128 their tiles leave room
+                             for two at a time and the other half of the workgroups follow as the first finish,
+                             which the even split allows) */
   int32_t mode;           /* DBSP_MODE_BALANCED: greedy longest-first placement (Alg. 1, first loop);
                              DBSP_MODE_NAIVE: items in row-major order dealt in contiguous runs of
                              ceil(n_items / P) -- the unbalanced baseline rho_s is quoted against;
@@ -70,7 +84,7 @@ typedef struct dbsp_plan_opts {
                              ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (2 P)); < 0 -> never split */
   int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
                              (rho_s is always computed from pure block counts). 0 = the paper's cost model */
-  int32_t flags;          /* DBSP_PLAN_HOST_ONLY or 0 */
+  int32_t flags;          /* DBSP_PLAN_HOST_ONLY | DBSP_PLAN_PAIR_ROWS, or 0 */
   int32_t locality_groups; /* DBSP_MODE_ROUNDS only: G > 1 keeps runs of neighbouring query blocks inside one
                              group of partitions that share a cache (partition p belongs to group p mod G;
                              on MI355X workgroup p runs on XCD p mod 8, each XCD has its own L2).  A round is

@@ -62,6 +62,38 @@ def compact(mask):
     return row_ptr, kv_idx
 
 
+def pair_rows(mask):
+    """Query blocks taken two at a time (for 64-token blocks served by 128-query workgroups: the
+    block size of the paper's PAROAttention masks, Methodology, "Block-level Partitioning").
+
+    Super-row (h, p) covers query blocks 2p and 2p+1 (the second may not exist when nQ is odd).
+    Its KV list is the ascending union of the two rows' active KV blocks, cut into consecutive
+    pairs ("super blocks", what one workgroup step streams): (j0, j1, flags) with flags bit
+    (q + 2k) set when query block 2p+q needs KV block j_k.  A union of odd length ends with a
+    super block whose second slot repeats j0 with no flag set.
+    Returns (cnt [H*ceil(nQ/2)] super blocks per super-row, row_ptr, list of (j0, j1, flags))."""
+    mask = np.asarray(mask)
+    H, nQ, nK = mask.shape
+    nQ2 = (nQ + 1) // 2
+    cnt, row_ptr, sbs = [], [0], []
+    for h in range(H):
+        for p in range(nQ2):
+            r0 = mask[h, 2 * p] != 0
+            r1 = mask[h, 2 * p + 1] != 0 if 2 * p + 1 < nQ else np.zeros(nK, dtype=bool)
+            union = [int(j) for j in np.flatnonzero(r0 | r1)]
+            need = lambda j: int(r0[j]) | (int(r1[j]) << 1)
+            for t in range(0, len(union), 2):
+                j0 = union[t]
+                if t + 1 < len(union):
+                    j1 = union[t + 1]
+                    sbs.append((j0, j1, need(j0) | (need(j1) << 2)))
+                else:
+                    sbs.append((j0, j0, need(j0)))
+            cnt.append((len(union) + 1) // 2)
+            row_ptr.append(len(sbs))
+    return cnt, row_ptr, sbs
+
+
 def auto_max_item_len(total_blocks: int, P: int) -> int:
     """Split threshold when the caller gives none: max(4, total // (2 P)).
 
@@ -303,7 +335,7 @@ def carry_over_partition(previous, items, nQ: int, P: int):
 
 def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_overhead: int = 0,
          previous=None, reuse_threshold: float = 1.0, locality_groups: int = 1, partition_cost=None,
-         dynamic_tail: int = 0, reward: float = 0.0):
+         dynamic_tail: int = 0, reward: float = 0.0, pair: bool = False):
     """Full plan as plain Python lists/ints (the arrays the library must reproduce bit-exactly).
 
     With `previous` (a plan of the same geometry and P), the previous placement is kept when the
@@ -311,11 +343,21 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     dynamic_tail (permille of the total weight, round-based placement only, not with a carried-over
     placement): the end of the item sequence goes to `tail_items`, a queue shared by all partitions,
     and is in no partition's list; part_load and rho_plan then cover the placed items only.
-    reward (MODE_REWARD only): the paper's R_b, see reward_partition."""
+    reward (MODE_REWARD only): the paper's R_b, see reward_partition.
+    pair: rows are the super-rows of pair_rows (two query blocks each) and the unit of work is the
+    super block; nQ, cnt, row_ptr, items, nnz are then in those units and kv_idx holds, per super
+    block, j0 and j1 | flags << 24."""
     mask = np.asarray(mask)
     H, nQ, nK = mask.shape
-    cnt, per_head, total = row_counts(mask)
-    row_ptr, kv_idx = compact(mask)
+    if pair:
+        cnt, row_ptr, sbs = pair_rows(mask)
+        nQ = (nQ + 1) // 2
+        per_head = [sum(cnt[h * nQ:(h + 1) * nQ]) for h in range(H)]
+        total = sum(cnt)
+        kv_idx = [v for (j0, j1, f) in sbs for v in (j0, j1 | (f << 24))]
+    else:
+        cnt, per_head, total = row_counts(mask)
+        row_ptr, kv_idx = compact(mask)
     L = auto_max_item_len(total, P) if max_item_len == 0 else max_item_len
     items, slot, split_rows = make_items(cnt, nQ, L)
     lens = [e - b for (_, _, b, e) in items]

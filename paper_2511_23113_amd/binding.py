@@ -17,6 +17,7 @@ from . import build as _build
 DBSP_OK, DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM, DBSP_EHIP = 0, -1, -2, -3, -4
 MODE_BALANCED, MODE_NAIVE, MODE_ROUNDS, MODE_REWARD = 0, 1, 2, 3
 PLAN_HOST_ONLY = 1
+PLAN_PAIR_ROWS = 2
 
 ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, BLOCKS_PER_HEAD, ROW_CNT, EMPTY_ROWS, TAIL_ITEMS = range(12)
 _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
@@ -102,9 +103,10 @@ def _check(rc: int):
 class Plan:
     """Owner of a dbsp_plan*; destroyed on close() or garbage collection."""
 
-    def __init__(self, handle: int, H: int, nQ: int, nK: int, block: int):
+    def __init__(self, handle: int, H: int, nQ: int, nK: int, block: int, pair_rows: bool = False):
         self._h = C.c_void_p(handle)
-        self.H, self.nQ, self.nK, self.block = H, nQ, nK, block
+        self.H, self.nQ, self.nK, self.block = H, nQ, nK, block      # nQ, nK: the mask's block grid
+        self.pair_rows = pair_rows
 
     @property
     def handle(self):
@@ -174,7 +176,7 @@ class Plan:
 def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
                      max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False,
                      locality_groups: int = 0, partition_cost=None, max_batch: int = 0, dynamic_tail: int = 0,
-                     reward: float = 0.0) -> Plan:
+                     reward: float = 0.0, pair_rows: bool = False) -> Plan:
     """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.ndim != 3:
@@ -186,11 +188,12 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
             num_partitions = int(cost.shape[0])      # one cost per partition: the array fixes their number
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
-    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
+    flags = (PLAN_HOST_ONLY if host_only else 0) | (PLAN_PAIR_ROWS if pair_rows else 0)
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, flags, locality_groups,
                     cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, float(reward))
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
-    return Plan(out.value, H, nQ, nK, block)
+    return Plan(out.value, H, nQ, nK, block, pair_rows)
 
 
 def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,
@@ -207,12 +210,14 @@ def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_par
             num_partitions = int(cost.shape[0])      # one cost per partition: the array fixes their number
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
-    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, PLAN_HOST_ONLY if host_only else 0, locality_groups,
+    flags = (PLAN_HOST_ONLY if host_only else 0) | (PLAN_PAIR_ROWS if previous.pair_rows else 0)   # pair rows are kept
+    opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, flags, locality_groups,
                     cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, 0.0)
     out, reused, rho = C.c_void_p(), C.c_int32(), C.c_double()
     _check(load_library().plan_sparse_attn_reuse(previous.handle, mask.ctypes.data_as(C.c_void_p), C.byref(opts),
                                                  float(reuse_threshold), C.byref(out), C.byref(reused), C.byref(rho)))
-    return Plan(out.value, previous.H, previous.nQ, previous.nK, previous.block), bool(reused.value), rho.value
+    return (Plan(out.value, previous.H, previous.nQ, previous.nK, previous.block, previous.pair_rows),
+            bool(reused.value), rho.value)
 
 
 def _stream_ptr(stream):

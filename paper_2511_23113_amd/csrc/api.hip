@@ -122,7 +122,7 @@ void free_device(dbsp_device_plan& d) {
 int get_kv_staging(dbsp_plan* plan) {
   dbsp_device_plan& dv = plan->dev;
   DBSP_HIP(hipGetDevice(&dv.device));
-  const size_t bytes = ((size_t)plan->host.nnz + 8) * sizeof(int32_t);
+  const size_t bytes = ((size_t)plan->host.kv_ints() + 8) * sizeof(int32_t);
   hipError_t e = pool_get(g_pin_pool, true, dv.device, bytes, &dv.staging_kv, &dv.staging_kv_bytes);
   if (e != hipSuccess) { (void)hipGetLastError(); return fail(DBSP_ENOMEM, std::string("plan staging buffer: ") + hipGetErrorString(e)); }
   return DBSP_OK;
@@ -147,9 +147,9 @@ int upload(dbsp_plan* plan) {
   const size_t queue_off = hw_off + (((size_t)hp.P * sizeof(uint32_t) + 255) & ~size_t(255));
   const size_t up_bytes = queue_off + (((2 + hp.tail_items.size()) * sizeof(uint32_t) + 255) & ~size_t(255));   // staged part ends here
   const size_t kv_off = up_bytes;
-  const size_t kv_bytes = (size_t)hp.nnz * sizeof(int32_t);
+  const size_t kv_bytes = (size_t)hp.kv_ints() * sizeof(int32_t);
   // split-row scratch for max_batch batch entries at d = 128
-  const int64_t rows = (int64_t)dv.max_batch * hp.n_slots * hp.block;
+  const int64_t rows = (int64_t)dv.max_batch * hp.n_slots * hp.tile_rows();
   const size_t lse_off = (kv_off + kv_bytes + 255) & ~size_t(255);
   const size_t po_off = lse_off + (((size_t)rows * sizeof(float) + 255) & ~size_t(255));
   const size_t total = po_off + (size_t)rows * 128 * sizeof(float);
@@ -240,13 +240,16 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   if (opts) o = *opts;
   if (o.num_partitions < 0 || o.item_overhead < 0 ||
       (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS && o.mode != DBSP_MODE_REWARD) ||
-      (o.flags & ~DBSP_PLAN_HOST_ONLY) || o.locality_groups < 0 || o.max_batch < 0)
+      (o.flags & ~(DBSP_PLAN_HOST_ONLY | DBSP_PLAN_PAIR_ROWS)) || o.locality_groups < 0 || o.max_batch < 0)
     return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, groups < 0, max_batch < 0, unknown mode or flag)");
   if (o.dynamic_tail < 0 || o.dynamic_tail >= 1000 || (o.dynamic_tail > 0 && o.mode != DBSP_MODE_ROUNDS))
     return fail(DBSP_EINVAL, std::string(who) + ": dynamic_tail is a permille in [0, 1000) and goes with DBSP_MODE_ROUNDS only");
   if (!(o.reward >= 0.0) || (o.reward != 0.0 && o.mode != DBSP_MODE_REWARD) || (o.mode == DBSP_MODE_REWARD && o.partition_cost))
     return fail(DBSP_EINVAL, std::string(who) + ": reward must be >= 0, goes with DBSP_MODE_REWARD only, and that mode takes no partition_cost");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
+  const bool pair = (o.flags & DBSP_PLAN_PAIR_ROWS) != 0;
+  if (pair && block != 64) return fail(DBSP_EINVAL, std::string(who) + ": DBSP_PLAN_PAIR_ROWS goes with 64-token blocks");
+  if (previous && previous->host.pair != pair) return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan differs in DBSP_PLAN_PAIR_ROWS");
   int32_t P = o.num_partitions;
   if (P == 0 && previous) P = previous->host.P;
   if (P == 0) {
@@ -260,10 +263,11 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
         (void)hipGetLastError();
     }
     // a 64-token block is served by a two-wave workgroup: four of them fill a compute unit at d = 64
-    // (at d = 128 two are resident at a time; the plan does not know d, and an even split runs in two rounds)
-    if (block <= 64) P *= 4;
+    // (at d = 128 two are resident at a time; the plan does not know d, and an even split runs in two rounds);
+    // pair rows are served by eight-wave workgroups, one per compute unit
+    if (block <= 64 && !pair) P *= 4;
   }
-  if (previous && (previous->host.H != H || previous->host.nQ != nQ || previous->host.nK != nK || previous->host.P != P))
+  if (previous && (previous->host.H != H || previous->host.nQ_blocks != nQ || previous->host.nK != nK || previous->host.P != P))
     return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan has a different geometry or partition count");
   if (o.locality_groups > 1 && P % o.locality_groups != 0)
     return fail(DBSP_EINVAL, std::string(who) + ": locality_groups must divide the number of partitions");
@@ -276,7 +280,7 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   dbsp_place_opts po;
   po.P = P; po.mode = o.mode; po.max_item_len = o.max_item_len; po.item_overhead = o.item_overhead;
   po.locality_groups = o.locality_groups; po.partition_cost = o.partition_cost;
-  po.dynamic_tail = o.dynamic_tail; po.reward = o.reward;
+  po.dynamic_tail = o.dynamic_tail; po.reward = o.reward; po.pair = pair;
   if (host_only) {
     int rc = dbsp_build_host_plan(mask_host, H, nQ, nK, block, po, previous ? &previous->host : nullptr, reuse_threshold, plan->host, err);
     if (rc != DBSP_OK) {
@@ -288,7 +292,7 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     // this thread builds the items and the placement; then everything is sent to the device
     dbsp_host_plan& hp = plan->host;
     plan->dev.max_batch = o.max_batch > 0 ? o.max_batch : 1;
-    int rc = dbsp_plan_count(mask_host, H, nQ, nK, block, hp, err);
+    int rc = dbsp_plan_count(mask_host, H, nQ, nK, block, pair, hp, err);
     if (rc != DBSP_OK) {
       delete plan;
       return fail(rc, std::string(who) + ": " + err);
@@ -340,7 +344,7 @@ int plan_sparse_attn_reuse(const dbsp_plan* previous, const uint8_t* mask_host, 
     return fail(DBSP_EINVAL, "plan_sparse_attn_reuse: the threshold must be at least 1");
   }
   const dbsp_host_plan& ph = previous->host;
-  int rc = make_plan(mask_host, ph.H, ph.nQ, ph.nK, ph.block, opts, previous, reuse_threshold, out_plan, "plan_sparse_attn_reuse");
+  int rc = make_plan(mask_host, ph.H, ph.nQ_blocks, ph.nK, ph.block, opts, previous, reuse_threshold, out_plan, "plan_sparse_attn_reuse");
   if (rc != DBSP_OK) return rc;
   if (reused) *reused = (*out_plan)->host.reused ? 1 : 0;
   if (rho_under_previous) *rho_under_previous = (*out_plan)->host.rho_reuse;
@@ -364,8 +368,9 @@ static int forward(const dbsp_plan* plan, const void* q, const void* k, const vo
   if (hp.block != 64 && hp.block != 128) return fail(DBSP_EINVAL, w + ": the plan's block size must be 64 or 128");
   if (Nq <= 0 || Nk <= 0 || Nq % hp.block != 0 || Nk % hp.block != 0)
     return fail(DBSP_ESHAPE, w + ": sequence lengths must be positive multiples of the block size");
-  if (Nq / hp.block != hp.nQ || Nk / hp.block != hp.nK)
+  if (Nq / hp.block != hp.nQ_blocks || Nk / hp.block != hp.nK)
     return fail(DBSP_ESHAPE, w + ": Nq/Nk do not match the plan's block grid");
+  if (hp.pair && d != 128) return fail(DBSP_EINVAL, w + ": a plan made with DBSP_PLAN_PAIR_ROWS needs head dim 128");
   if (!plan->dev.resident) return fail(DBSP_EINVAL, w + ": the plan was built host-only");
   if (!(softmax_scale == softmax_scale)) return fail(DBSP_EINVAL, w + ": softmax_scale is NaN");
   int cur = -1;
@@ -377,7 +382,7 @@ static int forward(const dbsp_plan* plan, const void* q, const void* k, const vo
   float* part_lse = dv.part_lse;
   if (static_scratch_wanted) {
     // partial outputs f32 [B][n_slots][block][d], then their LSE f32 [B][n_slots][block]
-    const size_t rows = (size_t)B * hp.n_slots * hp.block;
+    const size_t rows = (size_t)B * hp.n_slots * hp.tile_rows();
     const size_t lse_off = (rows * d * sizeof(float) + 255) & ~size_t(255);
     const size_t need = lse_off + rows * sizeof(float);
     if (need > kStaticScratchBytes)
@@ -414,6 +419,7 @@ static int forward(const dbsp_plan* plan, const void* q, const void* k, const vo
   p.busy = dv.busy;
   p.hw_id = dv.hw_id;
   p.B = B; p.H = hp.H; p.nQ = hp.nQ; p.nK = hp.nK;
+  p.Nq = Nq; p.Nk = Nk;
   p.n_slots = hp.n_slots;
   p.n_split = (int32_t)(hp.split_rows.size() / 4);
   p.n_empty = (int32_t)hp.empty_rows.size();
@@ -421,7 +427,7 @@ static int forward(const dbsp_plan* plan, const void* q, const void* k, const vo
   p.scale_log2 = p.scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);
   DBSP_HIP(hipStreamWaitEvent(st, static_cast<hipEvent_t>(dv.uploaded), 0));   // the plan's upload is asynchronous
-  hipError_t e = dbsp_launch_fwd(p, hp.block, d, hp.P, st);
+  hipError_t e = dbsp_launch_fwd(p, hp.block, d, hp.pair, hp.P, st);
   if (e != hipSuccess) return fail_hip(e, (w + " launch").c_str());
   DBSP_HIP(hipEventRecord(static_cast<hipEvent_t>(dv.last_use), st));
   plan->dev.used = true;
@@ -455,7 +461,7 @@ int dbsp_plan_get(const dbsp_plan* plan, int32_t what, const void** data, int64_
 #define DBSP_ARR(vec) do { *data = (vec).data(); *count = (int64_t)(vec).size(); return DBSP_OK; } while (0)
   switch (what) {
     case DBSP_ROW_PTR: DBSP_ARR(hp.row_ptr);
-    case DBSP_KV_IDX: *data = hp.kv_idx; *count = hp.nnz; return DBSP_OK;
+    case DBSP_KV_IDX: *data = hp.kv_idx; *count = hp.kv_ints(); return DBSP_OK;
     case DBSP_ITEMS: DBSP_ARR(hp.items);
     case DBSP_ITEM_SLOT: DBSP_ARR(hp.item_slot);
     case DBSP_SPLIT_ROWS: DBSP_ARR(hp.split_rows);

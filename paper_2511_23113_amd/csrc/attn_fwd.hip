@@ -24,6 +24,10 @@
 //     for that 16-key step.  The matching V^T operand comes from two transposing LDS reads
 //     (ds_read_b64_tr_b16) of row-major V: in a group of 16 lanes, lane 4j+a supplies the
 //     address of 4 consecutive d-values of key j, and lane i receives d-value i of 4 keys.
+// Pair mode (64-token mask blocks, the block size of the paper's PAROAttention masks, at d = 128):
+//   the eight-wave workgroup serves two neighbouring query blocks at once, and its KV tile is a pair
+//   of 64-token blocks from the union of the two rows' lists; each wave's (query block, KV block)
+//   combination carries a flag, and where it is clear the wave's probabilities are exact zeros.
 // Software pipeline:
 //   the unit of work is 32 keys x (32 QT) queries.  Step i issues, as independent work,
 //     the MFMAs of  K Q^T of unit i   and of  V^T P^T of unit i-2,  and
@@ -156,7 +160,7 @@ struct Cfg {
   static_assert(DT % 2 == 0, "the head dim is split between the two key-half waves at the end of an item");
 };
 
-template <int BLK, int D, int QT_>
+template <int BLK, int D, int QT_, bool PAIR>
 __global__ __launch_bounds__(BLK * BLK / (32 * QT_)) __attribute__((amdgpu_waves_per_eu(QT_ == 1 ? 2 : 1)))
 void dbsp_fwd_kernel(
     const dbsp_fwd_params p, const int32_t* __restrict__ g_row_ptr, const int32_t* __restrict__ g_kv_idx,
@@ -165,6 +169,7 @@ void dbsp_fwd_kernel(
   // the plan's index arrays are read-only for the whole launch: separate __restrict__ const
   // arguments let the compiler fetch them through the scalar unit
   using C = Cfg<BLK, D, QT_>;
+  static_assert(!PAIR || (BLK == 128 && D == 128 && QT_ == 1), "pair mode: two 64-token blocks per 128-row tile at d = 128");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   constexpr int K_OFF = 0, V_OFF = C::NKB * C::TILE_BYTES;   // byte offsets inside the dynamic LDS block
   const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
@@ -245,18 +250,44 @@ void dbsp_fwd_kernel(
       const int4 item = g_items[it];
       const int h = item.x, I = item.y;
       const int slot = g_item_slot[it];
-      const int32_t* __restrict__ kv = g_kv_idx + g_row_ptr[h * p.nQ + I] + item.z;   // this item's KV blocks
+      // this item's KV blocks (pair mode: two words per super block, see block_of / active_in below)
+      const int32_t* __restrict__ kv = g_kv_idx + (PAIR ? 2 : 1) * (g_row_ptr[h * p.nQ + I] + item.z);
       const int n_tiles = item.w - item.z;
       const int NU = n_tiles * C::U;                                                  // pipeline units
       const int64_t bh = (int64_t)bb * p.H + h;
-      const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k + bh * p.nK * BLK * D);
-      const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v + bh * p.nK * BLK * D);
+      const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k + (PAIR ? bh * p.Nk * D : bh * p.nK * BLK * D));
+      const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v + (PAIR ? bh * p.Nk * D : bh * p.nK * BLK * D));
+      // Pair mode: a 128-row tile is two 64-token mask blocks.  Tile T of the item is the super block
+      // (j0, j1) = (kv[2T], kv[2T+1] & 0xffffff) with a flag per (query block, KV block) combination in
+      // kv[2T+1] >> 24, bit q + 2k.  Wave (wa, wc) works on query block wa / 2 and KV block wc of every
+      // super block.  Where its flag is clear it runs the block's stages like everybody (no branches
+      // in the step sequence) and forms its probabilities against a running max of +inf, that is, as
+      // exact zeros, so the block adds nothing to its sums and its accumulator.  (Leaving those
+      // stages out instead, with wave-uniform branches around every group of MFMAs, LDS reads and
+      // softmax work, measured 22 % slower with all flags set and no faster at 57 % of them set.)
+      // The K / V rows this wave copies (16 w .. 16 w + 15 of the tile) come from block j0 for the
+      // first four waves, from j1 for the others.
+      auto block_of = [&](int T) -> int {
+        if constexpr (PAIR) return (w < C::NW / 2) ? kv[2 * T] : (kv[2 * T + 1] & 0xffffff);
+        else return kv[T];
+      };
+      const int flag_bit = 24 + (wa >> 1) + 2 * wc;
+      [[maybe_unused]] auto active_in = [&](int T) -> bool { return ((kv[2 * T + 1] >> flag_bit) & 1) != 0; };
+      // this wave's flags of the blocks before, at, after and two after the K Q^T stage's block;
+      // the last is fetched next to the id of the same block (see the barrier step), two blocks
+      // ahead, so that no step waits for the scalar load
+      [[maybe_unused]] bool a_prev = false, a_cur = true, a_next = true, a_next2 = true;
+      if constexpr (PAIR) {
+        a_cur = active_in(0);
+        a_next = (1 < n_tiles) && active_in(1);
+      }
 
       // byte offset of this wave's share inside a tile, same in global memory and in LDS
       const uint32_t wave_off = w * C::LOADS * 1024;
       // one wave's share of a tile: LOADS copies of 1 KiB, in groups of four that share an M0 and a base
       auto copy_k_tile = [&](int J, int buf) {
-        const unsigned char* from = kbase + (int64_t)J * C::TILE_BYTES + wave_off;
+        const unsigned char* from = PAIR ? kbase + (int64_t)J * (C::TILE_BYTES / 2) + (wave_off & (C::TILE_BYTES / 2 - 1))
+                                         : kbase + (int64_t)J * C::TILE_BYTES + wave_off;
         const uint32_t to = lds_base + K_OFF + buf * C::TILE_BYTES + wave_off;
 #pragma unroll
         for (int n = 0; n < C::LOADS; ++n) {
@@ -265,7 +296,8 @@ void dbsp_fwd_kernel(
         }
       };
       auto copy_v_tile = [&](int J, int buf) {
-        const unsigned char* from = vbase + (int64_t)J * C::TILE_BYTES + wave_off;
+        const unsigned char* from = PAIR ? vbase + (int64_t)J * (C::TILE_BYTES / 2) + (wave_off & (C::TILE_BYTES / 2 - 1))
+                                         : vbase + (int64_t)J * C::TILE_BYTES + wave_off;
         const uint32_t to = lds_base + V_OFF + buf * C::TILE_BYTES + wave_off;
 #pragma unroll
         for (int n = 0; n < C::LOADS; ++n) {
@@ -277,16 +309,20 @@ void dbsp_fwd_kernel(
       // 0 are copied here; from then on the barrier in the middle of block T's second step is
       // followed by the copies of K of block T+2 and V of block T+1, into the buffers whose last
       // reads that barrier has just retired: every copy has two steps to land.
-      copy_k_tile(kv[0], 0);
-      if (n_tiles > 1) copy_k_tile(kv[1], 1);
-      copy_v_tile(kv[0], 0);
+      copy_k_tile(block_of(0), 0);
+      if (n_tiles > 1) copy_k_tile(block_of(1), 1);
+      copy_v_tile(block_of(0), 0);
 
       // Q^T operands of this wave's 64 queries: lane (r, g) holds q[32*qt + r][16ks + 8g .. +7]
       const int q0 = 32 * C::QT * wa;
       bf16x8 qreg[C::QT][C::KS_QK];
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt) {
-        const uint16_t* qrow = p.q + (bh * p.nQ * BLK + (int64_t)I * BLK + q0 + 32 * qt + r) * D;
+        // pair mode: the last pair of a head may lack its second query block; its waves load some
+        // valid row instead, work on nothing (all their flags are clear) and store nothing
+        const int tq = I * BLK + q0 + 32 * qt + r;
+        const uint16_t* qrow = PAIR ? p.q + (bh * p.Nq + (tq < p.Nq ? tq : p.Nq - 1)) * D
+                                    : p.q + (bh * p.nQ * BLK + (int64_t)I * BLK + q0 + 32 * qt + r) * D;
 #pragma unroll
         for (int ks = 0; ks < C::KS_QK; ++ks)
           qreg[qt][ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 16 * ks + 8 * g));
@@ -341,7 +377,7 @@ void dbsp_fwd_kernel(
       };
 
       // id of the block whose V is copied after the next barrier (the block whose K went last)
-      int j_v = kv[(1 < n_tiles) ? 1 : 0];
+      int j_v = block_of((1 < n_tiles) ? 1 : 0);
 
       // One pipeline step.  PAR = parity of the step = half of the KV block its K Q^T unit covers;
       // QK / SM / PV say which stages are live (all three in the steady state; fewer while the
@@ -358,6 +394,10 @@ void dbsp_fwd_kernel(
         constexpr bool QK = decltype(qk_tag)::value, SM = decltype(sm_tag)::value, PV = decltype(pv_tag)::value;
         constexpr bool NQK = decltype(nqk_tag)::value, NPV = decltype(npv_tag)::value;
         constexpr int HALF = PAR, NHALF = 1 - PAR;
+        constexpr bool BAR = QK && HALF == 1;     // the step holds the barrier of its KV block
+        // pair mode: does the softmax stage's unit belong to a block this wave works on?  It is in
+        // the K Q^T stage's block for the second step of a block, in the block before for the first.
+        const bool ls = !PAIR || (PAR == 1 ? a_cur : a_prev);
         const int Tq = i / C::U;                             // block of the K Q^T stage's unit
         const int Tp = (i - 2) / C::U;                       // block of the V^T P^T stage's unit
         static_assert(C::NKB == 2 && C::NVB == 2, "buffer parities below assume double buffering");
@@ -376,13 +416,19 @@ void dbsp_fwd_kernel(
         bool pend = false;
         float l_spec[C::QT], ls0[C::QT], ls1[C::QT];
         uint32_t pw[C::QT][4];
+        float mc_eff[C::QT];     // the running max the probabilities are formed against
+#pragma unroll
+        for (int qt = 0; qt < C::QT; ++qt) {
+          mc_eff[qt] = mc_run[qt];
+          if constexpr (PAIR) mc_eff[qt] = ls ? mc_run[qt] : INFINITY;   // not this wave's block: exp2(-inf) = 0
+        }
         auto softmax_chunk = [&](int j) {     // j = 0..7: scores 2j and 2j+1 of every tile
           const int hf = j / 4, e2 = j % 4;
 #pragma unroll
           for (int qt = 0; qt < C::QT; ++qt) {
             const f32x16& sv = S[1 - PAR][qt];
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc_run[qt]));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc_run[qt]));
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2], c, -mc_eff[qt]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * hf + 2 * e2 + 1], c, -mc_eff[qt]));
             if (j == 0) { ls0[qt] = p0; ls1[qt] = p1; }      // no "0 + p" to start the two chains
             else { ls0[qt] += p0; ls1[qt] += p1; }
             pw[qt][e2] = pack_bf16x2(p0, p1);
@@ -464,13 +510,17 @@ void dbsp_fwd_kernel(
 #pragma unroll
             for (int cc = 0; cc < CPS; ++cc) softmax_chunk(x * CPS + cc);
           }
-          if constexpr (QK && HALF == 1) {
+          if constexpr (BAR) {
             // id of the block whose K is copied after the barrier below, through the scalar cache
-            if (x == SLOTS - 1) jk = kv[(Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1];
+            // (pair mode: and this wave's flag of that block)
+            if (x == SLOTS - 1) {
+              jk = block_of((Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1);
+              if constexpr (PAIR) a_next2 = (Tq + 2 < n_tiles) && active_in(Tq + 2);
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (QK && HALF == 1) {
+        if constexpr (BAR) {
           // One barrier per KV block.  Before it, this wave's copies have landed and its reads of
           // block Tq's K and block Tq-1's V are complete; after it, everybody's: K of block Tq+1 and
           // V of block Tq may be read, and the two retired buffers are refilled.
@@ -497,6 +547,7 @@ void dbsp_fwd_kernel(
           }
           __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (PAIR && BAR) { a_prev = a_cur; a_cur = a_next; a_next = a_next2; }   // on to the next block
 
         // ---- slow path: raise the running max, redo the probabilities, rescale the accumulator
         //      (after V^T P^T of unit i-2, before that of unit i-1) ------------------------------
@@ -559,11 +610,15 @@ void dbsp_fwd_kernel(
 
       // ---- end of item: combine the key halves (if the block has two) and store ----------------
       __syncthreads();   // every wave is done reading the K/V tiles: the buffers become the exchange area
-      const int64_t tok0 = bh * p.nQ * BLK + (int64_t)I * BLK + q0 + r;
+      const int64_t tok0 = PAIR ? bh * p.Nq + (int64_t)I * BLK + q0 + r : bh * p.nQ * BLK + (int64_t)I * BLK + q0 + r;
+      // pair mode: false for the waves of a query block past the end of the head (they still fill
+      // their rows of a split row's partial result: zeros and -inf)
+      const bool q_there = !PAIR || I * BLK + q0 < p.Nq;
       const int64_t ps = (int64_t)bb * p.n_slots + slot;
       // stores 16 values of one 32x32 tile of O^T: query tok, d = 32*dt + 8*(e/4) + 4*g + e%4
       auto store_tile = [&](const float (&res)[16], int64_t tok, int qloc, int dt) {
         if (slot < 0) {
+          if (!q_there) return;
           uint16_t* orow = p.o + tok * D + 32 * dt + 4 * g;
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
@@ -582,7 +637,7 @@ void dbsp_fwd_kernel(
         }
       };
       auto store_lse = [&](float lse, int64_t tok, int qloc) {
-        if (slot < 0) { if (p.lse != nullptr) p.lse[tok] = lse; }
+        if (slot < 0) { if (p.lse != nullptr && q_there) p.lse[tok] = lse; }
         else p.part_lse[ps * BLK + qloc] = lse;
       };
 
@@ -629,10 +684,13 @@ void dbsp_fwd_kernel(
           for (int qt = 0; qt < C::QT; ++qt) {
             const float mp = ys[(2 * qt + 0) * 64 + l], lp = ys[(2 * qt + 1) * 64 + l];
             const float mt = fmaxf(m_run[qt], mp);
-            const float fs = __builtin_amdgcn_exp2f((m_run[qt] - mt) * c);
-            const float fp = __builtin_amdgcn_exp2f((mp - mt) * c);
+            // pair mode: a query block may have nothing in this item (both halves at -inf, sums 0):
+            // its rows come out as O = 0, LSE = -inf, without forming inf - inf or 0 / 0
+            const float mref = (PAIR && mt == -INFINITY) ? 0.f : mt;
+            const float fs = __builtin_amdgcn_exp2f((m_run[qt] - mref) * c);
+            const float fp = __builtin_amdgcn_exp2f((mp - mref) * c);
             const float lt = l_full[qt] * fs + lp * fp;
-            const float inv = 1.0f / lt;
+            const float inv = (PAIR && !(lt > 0.f)) ? 0.f : 1.0f / lt;
             const float fsi = fs * inv, fpi = fp * inv;
             const int64_t tok = tok0 + 32 * qt;
 #pragma unroll
@@ -679,6 +737,8 @@ void dbsp_fwd_kernel(
 // Grid: (B * (n_split + n_empty), blk * D / 4 / 256) workgroups of 256 threads; a thread produces four
 // consecutive d-values of one query (all its loads are independent of each other: the pass is
 // bandwidth-bound, not latency-bound).
+// blk = query rows of a plan row (pair mode: 128, where the last row of a head may reach past Nq
+// by one 64-token block and a query block may have no active block in some or all chunks).
 template <int D>
 __global__ __launch_bounds__(256) void dbsp_fixup_kernel(const dbsp_fwd_params p, int blk) {
   const int per_b = p.n_split + p.n_empty;
@@ -691,18 +751,21 @@ __global__ __launch_bounds__(256) void dbsp_fixup_kernel(const dbsp_fwd_params p
     const int h = row / p.nQ, I = row % p.nQ;
     const int64_t bh = (int64_t)bb * p.H + h;
     const int64_t ps0 = (int64_t)bb * p.n_slots + first;
+    if (I * blk + qloc >= p.Nq) return;
     float mx = -INFINITY;
     for (int kx = 0; kx < nch; ++kx) mx = fmaxf(mx, p.part_lse[(ps0 + kx) * blk + qloc]);
+    const bool none = (mx == -INFINITY);      // no chunk has anything for this query: O = 0, LSE = -inf
+    const float mref = none ? 0.f : mx;
     float tot = 0.f;
-    for (int kx = 0; kx < nch; ++kx) tot += __expf(p.part_lse[(ps0 + kx) * blk + qloc] - mx);
-    const float lse = mx + __logf(tot);
+    for (int kx = 0; kx < nch; ++kx) tot += __expf(p.part_lse[(ps0 + kx) * blk + qloc] - mref);
+    const float lse = none ? -INFINITY : mx + __logf(tot);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int kx = 0; kx < nch; ++kx) {
-      const float wgt = __expf(p.part_lse[(ps0 + kx) * blk + qloc] - lse);
+      const float wgt = none ? 0.f : __expf(p.part_lse[(ps0 + kx) * blk + qloc] - lse);
       const f32x4 f = *reinterpret_cast<const f32x4*>(p.part_o + ((ps0 + kx) * blk + qloc) * D + 4 * d4);
       acc.x += wgt * f.x;  acc.y += wgt * f.y;  acc.z += wgt * f.z;  acc.w += wgt * f.w;
     }
-    const int64_t tok = bh * p.nQ * blk + (int64_t)I * blk + qloc;
+    const int64_t tok = bh * p.Nq + (int64_t)I * blk + qloc;
     u32x2 pk;
     pk.x = pack_bf16x2(acc.x, acc.y);
     pk.y = pack_bf16x2(acc.z, acc.w);
@@ -712,13 +775,14 @@ __global__ __launch_bounds__(256) void dbsp_fixup_kernel(const dbsp_fwd_params p
     const int row = p.empty_rows[e - p.n_split];
     const int h = row / p.nQ, I = row % p.nQ;
     const int64_t bh = (int64_t)bb * p.H + h;
-    const int64_t tok = bh * p.nQ * blk + (int64_t)I * blk + qloc;
+    if (I * blk + qloc >= p.Nq) return;
+    const int64_t tok = bh * p.Nq + (int64_t)I * blk + qloc;
     *reinterpret_cast<u32x2*>(p.o + tok * D + 4 * d4) = u32x2{0u, 0u};
     if (p.lse != nullptr && d4 == 0) p.lse[tok] = -INFINITY;
   }
 }
 
-template <int BLK, int D, int QT_>
+template <int BLK, int D, int QT_, bool PAIR = false>
 hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
   using C = Cfg<BLK, D, QT_>;
   // the dynamic-LDS limit is a per-device function attribute: set it once per device
@@ -728,22 +792,24 @@ hipError_t launch_fwd(const dbsp_fwd_params& p, int P, hipStream_t stream) {
   if (e != hipSuccess) return e;
   const uint32_t bit = 1u << (dev & 31);
   if (!(attr_set_mask.load(std::memory_order_acquire) & bit)) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbsp_fwd_kernel<BLK, D, QT_>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbsp_fwd_kernel<BLK, D, QT_, PAIR>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set_mask.fetch_or(bit, std::memory_order_release);
   }
-  hipLaunchKernelGGL((dbsp_fwd_kernel<BLK, D, QT_>), dim3(P), dim3(C::NT), C::LDS_BYTES, stream, p, p.row_ptr, p.kv_idx,
+  hipLaunchKernelGGL((dbsp_fwd_kernel<BLK, D, QT_, PAIR>), dim3(P), dim3(C::NT), C::LDS_BYTES, stream, p, p.row_ptr, p.kv_idx,
                      reinterpret_cast<const int4*>(p.items), p.item_slot, p.part_ptr, p.part_items);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, int P, hipStream_t stream) {
+hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, bool pair, int P, hipStream_t stream) {
   hipError_t e;
+  if (pair && (block != 64 || d != 128)) return hipErrorInvalidValue;
   // waves of 32 queries everywhere: eight per workgroup for 128-token blocks, two for 64-token blocks
-  if (block == 128 && d == 128) e = launch_fwd<128, 128, 1>(p, P, stream);
+  if (pair) { e = launch_fwd<128, 128, 1, true>(p, P, stream); block = 128; }
+  else if (block == 128 && d == 128) e = launch_fwd<128, 128, 1>(p, P, stream);
   else if (block == 128 && d == 64) e = launch_fwd<128, 64, 1>(p, P, stream);
   else if (block == 64 && d == 128) e = launch_fwd<64, 128, 1>(p, P, stream);
   else if (block == 64 && d == 64) e = launch_fwd<64, 64, 1>(p, P, stream);

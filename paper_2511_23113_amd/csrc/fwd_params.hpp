@@ -25,11 +25,13 @@ struct dbsp_fwd_params {
   float* part_lse;     // f32 [B][n_slots][BLK]
   uint64_t* busy;      // [P]
   uint32_t* hw_id;     // [P]
-  int32_t B, H, nQ, nK;
+  int32_t B, H, nQ, nK;     // nQ: rows per head of the plan (pair mode: pairs of query blocks); nK: KV blocks
+  int32_t Nq, Nk;           // tokens per head
   int32_t n_slots, n_split, n_empty, n_tail;
   float scale;         // softmax scale
   float scale_log2;    // softmax scale * log2(e)
 };
 
 // Enqueues the persistent kernel (grid = P workgroups) and, if needed, the fix-up kernel.
-hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, int P, hipStream_t stream);
+// pair: the plan's rows are pairs of 64-token query blocks and its units pairs of 64-token KV blocks (d = 128 only).
+hipError_t dbsp_launch_fwd(const dbsp_fwd_params& p, int block, int d, bool pair, int P, hipStream_t stream);

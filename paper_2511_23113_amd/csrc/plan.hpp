@@ -10,13 +10,15 @@
 #include "dbsp.h"
 
 struct dbsp_host_plan {
-  int32_t H = 0, nQ = 0, nK = 0, block = 0;
+  int32_t H = 0, nQ = 0, nK = 0, block = 0;   // nQ: rows per head of the PLAN (pair mode: pairs of query blocks)
+  bool pair = false;                          // pair mode: a row is two query blocks, a unit of work a pair of KV blocks
+  int32_t nQ_blocks = 0;                      // query blocks per head of the MASK
   int32_t P = 0, mode = 0, max_item_len = 0, item_overhead = 0;
   int64_t nnz = 0;
   std::vector<int32_t> row_cnt;          // [R]
   std::vector<int64_t> blocks_per_head;  // [H]
   std::vector<int32_t> row_ptr;          // [R+1]
-  const int32_t* kv_idx = nullptr;       // [nnz]: in kv_store (host-only plans) or in the plan's pinned staging buffer
+  const int32_t* kv_idx = nullptr;       // [nnz] (pair mode: [2 nnz], j0 and j1 | flags << 24 per super block): in kv_store (host-only plans) or in the plan's pinned staging buffer
   std::vector<int32_t> kv_store;
   std::vector<int32_t> items;            // [n_items*4]
   std::vector<int32_t> item_slot;        // [n_items]
@@ -36,6 +38,8 @@ struct dbsp_host_plan {
   bool reused = false;       // the placement was carried over from a previous plan
   double rho_reuse = 0.0;    // rho_s of this mask under the previous plan's placement (0 if none was tried)
   int64_t n_items() const { return (int64_t)item_slot.size(); }
+  int64_t kv_ints() const { return pair ? 2 * nnz : nnz; }   // length of kv_idx
+  int32_t tile_rows() const { return pair ? 2 * block : block; }   // query rows one work item covers
 };
 
 // Device mirror.  One pooled allocation (`blob`) holds the int32 arrays, the busy-time capture
@@ -90,6 +94,7 @@ struct dbsp_plan {
 struct dbsp_place_opts {
   int32_t P = 0, mode = 0, max_item_len = 0, item_overhead = 0, locality_groups = 0;
   const int32_t* partition_cost = nullptr;
+  bool pair = false;          // pair mode (see dbsp_host_plan)
   int32_t dynamic_tail = 0;   // permille of the total weight left to the shared queue (round-based placement)
   double reward = 0.0;        // R_b of DBSP_MODE_REWARD
 };
@@ -98,7 +103,7 @@ struct dbsp_compaction {
   void* pool = nullptr;    // set between begin and end
   void* state = nullptr;
 };
-int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block, dbsp_host_plan& out, std::string& err);
+int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ_blocks, int32_t nK, int32_t block, bool pair, dbsp_host_plan& out, std::string& err);
 void dbsp_compact_begin(const uint8_t* mask, const dbsp_host_plan& hp, int32_t* dst, dbsp_compaction& job);
 bool dbsp_compact_end(dbsp_compaction& job);
 int dbsp_plan_place(const dbsp_place_opts& opts, const dbsp_host_plan* prev, double reuse_threshold,

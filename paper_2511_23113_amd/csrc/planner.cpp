@@ -85,6 +85,39 @@ inline int32_t* compact_row(const uint8_t* row, int32_t n, int32_t* out) {
   return out;
 }
 
+// Pair mode (two query blocks per row): number of KV blocks either of the two mask rows needs.
+inline int32_t count_union(const uint8_t* row0, const uint8_t* row1, int32_t n) {
+  if (!row1) return count_row(row0, n);
+  int32_t c = 0, j = 0;
+  for (; j + 8 <= n; j += 8) {
+    uint64_t a, b;
+    std::memcpy(&a, row0 + j, 8);
+    std::memcpy(&b, row1 + j, 8);
+    c += __builtin_popcountll(nonzero_bytes(a) | nonzero_bytes(b));
+  }
+  for (; j < n; ++j) c += (row0[j] | row1[j]) != 0;
+  return c;
+}
+
+// Pair mode: the super blocks of one super-row: consecutive pairs (j0, j1) of the ascending union of
+// the two rows' KV blocks, stored as j0 and j1 | flags << 24, flags bit (q + 2k) = "query block q
+// needs KV block j_k".  A union of odd length ends with j1 = j0 and no flag for the second slot.
+inline void compact_pair(const uint8_t* row0, const uint8_t* row1, int32_t n, int32_t* out) {
+  int32_t have = -1, have_f = 0;
+  for (int32_t j = 0; j < n; ++j) {
+    const int32_t f = (row0[j] != 0 ? 1 : 0) | ((row1 && row1[j] != 0) ? 2 : 0);
+    if (!f) continue;
+    if (have < 0) { have = j; have_f = f; continue; }
+    *out++ = have;
+    *out++ = j | ((have_f | (f << 2)) << 24);
+    have = -1;
+  }
+  if (have >= 0) {
+    *out++ = have;
+    *out++ = have | (have_f << 24);
+  }
+}
+
 // Binary min-heap over partitions keyed by (load, index): the root is the least-loaded
 // partition, lowest index among equals.  Only the root's key ever grows, so one sift-down
 // per placement is enough.
@@ -376,18 +409,28 @@ int row_threads(int64_t mask_bytes) {
 }
 }  // namespace
 
-int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block, dbsp_host_plan& hp, std::string& err) {
+int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ_blocks, int32_t nK, int32_t block, bool pair, dbsp_host_plan& hp, std::string& err) {
   try {
+    // pair mode: a row of the plan is two query blocks of the mask, and what is counted are super
+    // blocks (pairs of KV blocks of the union list)
+    const int32_t nQ = pair ? (nQ_blocks + 1) / 2 : nQ_blocks;
     const int64_t R = (int64_t)H * nQ;
+    if (pair && nK >= (1 << 24)) { err = "pair mode packs flags above 24 bits of a KV block id"; return DBSP_EINVAL; }
     hp.H = H; hp.nQ = nQ; hp.nK = nK; hp.block = block;
+    hp.pair = pair; hp.nQ_blocks = nQ_blocks;
     // per-row counts (Alg. 1's get_blocks_per_head, kept per row), row offsets.  Rows are
     // independent: large masks are cut into contiguous row ranges, one per thread.
     hp.row_cnt.resize(R);
     hp.row_ptr.resize(R + 1);
     hp.blocks_per_head.assign(H, 0);
-    const int n_thr = row_threads(R * nK);
+    const int n_thr = row_threads((int64_t)H * nQ_blocks * nK);
     const std::function<void(int)> job = [&](int k) {
-      for (int64_t r = R * k / n_thr; r < R * (k + 1) / n_thr; ++r) hp.row_cnt[r] = count_row(mask + r * nK, nK);
+      for (int64_t r = R * k / n_thr; r < R * (k + 1) / n_thr; ++r) {
+        if (!pair) { hp.row_cnt[r] = count_row(mask + r * nK, nK); continue; }
+        const int64_t h = r / nQ, q0 = 2 * (r % nQ);
+        const uint8_t* row0 = mask + (h * nQ_blocks + q0) * nK;
+        hp.row_cnt[r] = (count_union(row0, q0 + 1 < nQ_blocks ? row0 + nK : nullptr, nK) + 1) / 2;
+      }
     };
     if (n_thr <= 1) job(0);
     else if (!RowPool::instance().run(n_thr, job)) { err = "out of host memory while planning"; return DBSP_ENOMEM; }
@@ -414,11 +457,20 @@ int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int3
 void dbsp_compact_begin(const uint8_t* mask, const dbsp_host_plan& hp, int32_t* dst, dbsp_compaction& job) {
   const int64_t R = (int64_t)hp.H * hp.nQ;
   const int32_t nK = hp.nK;
-  const int n_thr = row_threads(R * nK);
+  const int n_thr = row_threads((int64_t)hp.H * hp.nQ_blocks * nK);
   const dbsp_host_plan* php = &hp;
   job.body = [=](int k) {
     const dbsp_host_plan& h = *php;
     const int64_t r0 = R * k / n_thr, r1 = R * (k + 1) / n_thr;
+    if (h.pair) {     // two ints per super block, written exactly: no slack between rows needed
+      for (int64_t r = r0; r < r1; ++r) {
+        if (!h.row_cnt[r]) continue;
+        const int64_t hd = r / h.nQ, q0 = 2 * (r % h.nQ);
+        const uint8_t* row0 = mask + (hd * h.nQ_blocks + q0) * nK;
+        compact_pair(row0, q0 + 1 < h.nQ_blocks ? row0 + nK : nullptr, nK, dst + 2 * (int64_t)h.row_ptr[r]);
+      }
+      return;
+    }
     std::vector<int32_t> bounce;
     for (int64_t r = r0; r < r1; ++r) {
       if (!h.row_cnt[r]) continue;
@@ -431,7 +483,7 @@ void dbsp_compact_begin(const uint8_t* mask, const dbsp_host_plan& hp, int32_t* 
       }
     }
   };
-  if (n_thr <= 1 && R * nK < ((int64_t)1 << 18)) {   // a small mask: done before a helper thread would have woken up
+  if (n_thr <= 1 && (int64_t)hp.H * hp.nQ_blocks * nK < ((int64_t)1 << 18)) {   // a small mask: done before a helper thread would have woken up
     job.pool = nullptr;
     job.body(0);
     return;
@@ -693,10 +745,10 @@ int dbsp_plan_place(const dbsp_place_opts& opts, const dbsp_host_plan* prev, dou
 int dbsp_build_host_plan(const uint8_t* mask, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                          const dbsp_place_opts& opts, const dbsp_host_plan* prev,
                          double reuse_threshold, dbsp_host_plan& hp, std::string& err) {
-  int rc = dbsp_plan_count(mask, H, nQ, nK, block, hp, err);
+  int rc = dbsp_plan_count(mask, H, nQ, nK, block, opts.pair, hp, err);
   if (rc != DBSP_OK) return rc;
   try {
-    hp.kv_store.resize(hp.nnz + 8);
+    hp.kv_store.resize(hp.kv_ints() + 8);
   } catch (const std::bad_alloc&) {
     err = "out of host memory while planning";
     return DBSP_ENOMEM;

@@ -13,4 +13,5 @@ from .masks import (  # noqa: F401
     mask_for_config,
     mask_sequence_cfg5,
     random_mask,
+    refine_to_half_blocks,
 )

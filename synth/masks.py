@@ -193,3 +193,16 @@ def imbalance_sweep_mask(rho_target: float, seed: int = 0) -> np.ndarray:
         m[np.arange(n), np.arange(n)] = 1
         _fill_to_count(m, int(round((d_hi if k < heavy else d_lo) * n * n)), rng)
     return mask
+
+
+def refine_to_half_blocks(mask: np.ndarray, keep: float, seed: int = 0) -> np.ndarray:
+    """A mask at half the block size: every active block becomes 2 x 2 blocks, each kept with
+    probability `keep` (independently; a block may lose all four).  Stands in for masks built at
+    64-token granularity (the paper's PAROAttention block size) on a workload whose recipe is
+    stated at 128: keep = 1 is the same set of token pairs, lower values add fine-grained holes.
+    The draw is one PCG64 stream seeded with 7100 + seed."""
+    rng = np.random.Generator(np.random.PCG64(7100 + seed))
+    fine = np.repeat(np.repeat(np.asarray(mask) != 0, 2, axis=1), 2, axis=2)
+    if keep < 1.0:
+        fine &= rng.random(fine.shape) < keep
+    return fine.astype(np.uint8)

@@ -91,11 +91,11 @@ def test_imbalance_ratio_matches_oracle_and_hand_values():
         assert B.imbalance_ratio(w) == op.imbalance_ratio(w.tolist())
 
 
-def _assert_plan_equal(mask, block, P, mode, L, c0, G=0, cost=None, tail=0, reward=0.0):
+def _assert_plan_equal(mask, block, P, mode, L, c0, G=0, cost=None, tail=0, reward=0.0, pair=False):
     pl = B.plan_sparse_attn(mask, block, num_partitions=P, mode=mode, max_item_len=L, item_overhead=c0, host_only=True,
-                            locality_groups=G, partition_cost=cost, dynamic_tail=tail, reward=reward)
+                            locality_groups=G, partition_cost=cost, dynamic_tail=tail, reward=reward, pair_rows=pair)
     ref = op.plan(mask, P, mode=mode, max_item_len=L, item_overhead=c0, locality_groups=G, partition_cost=cost,
-                  dynamic_tail=tail, reward=reward)
+                  dynamic_tail=tail, reward=reward, pair=pair)
     st = pl.stats()
     assert st["nnz"] == ref["nnz"] and st["n_items"] == len(ref["items"])
     assert st["num_partitions"] == P and st["max_item_len"] == ref["max_item_len"]
@@ -413,3 +413,39 @@ def test_reward_mode_bit_exact_and_errors():
            B.PlanOpts(4, B.MODE_REWARD, 0, 0, B.PLAN_HOST_ONLY, 3, None, 0, 0, 1.0))
     for o in bad:
         assert _plan_raw(mp, 1, 2, 2, 64, o)[0] == B.DBSP_EINVAL
+
+
+def test_pair_rows_bit_exact_reuse_and_errors():
+    # 64-token blocks served two query blocks at a time: rows, counts and lists are those of pairs and super blocks
+    rng = np.random.default_rng(8)
+    for seed in range(24):
+        H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 14)), int(rng.integers(1, 30))
+        mask = synth.random_mask(H, nQ, nK, float(rng.uniform(0, 1)), seed=seed)
+        if seed % 4 == 0 and nQ > 2:
+            mask[:, 2:4] = 0
+        P = int(rng.choice([1, 3, 4, 8]))
+        mode = (B.MODE_BALANCED, B.MODE_NAIVE, B.MODE_ROUNDS)[seed % 3]
+        tail = int(rng.integers(1, 500)) if mode == B.MODE_ROUNDS and seed % 2 else 0
+        _assert_plan_equal(mask, 64, P, mode, int(rng.choice([0, 1, 2, -1])), int(rng.integers(0, 3)), 1 if tail else 0, None, tail, 0.0, True)
+    cog = synth.mask_for_config(2)                      # 275 query blocks per head: an odd number
+    _assert_plan_equal(cog, 64, 256, B.MODE_ROUNDS, 0, 0, 8, None, 40, 0.0, True)
+    _assert_plan_equal(cog, 64, 256, B.MODE_BALANCED, 0, 0, 0, None, 0, 0.0, True)
+    # the placement is carried over between pair-row plans like between plain ones
+    m0, m1 = synth.random_mask(2, 7, 20, 0.5, seed=1), synth.random_mask(2, 7, 20, 0.5, seed=2)
+    prev = B.plan_sparse_attn(m0, 64, num_partitions=4, host_only=True, pair_rows=True)
+    ref_prev = op.plan(m0, 4, pair=True)
+    nxt, reused, rho = B.plan_sparse_attn_reuse(prev, m1, 3.0, host_only=True)
+    ref = op.plan(m1, 4, pair=True, previous=ref_prev, reuse_threshold=3.0)
+    assert reused == ref["reused"] and rho == ref["rho_reuse"] and nxt.pair_rows
+    assert nxt.array(B.PART_ITEMS).tolist() == list(ref["part_items"]) and nxt.array(B.KV_IDX).tolist() == list(ref["kv_idx"])
+    # a plain plan cannot follow a pair-row plan, 128-token blocks have no pair rows
+    lib = B.load_library()
+    out = C.c_void_p()
+    plain = B.PlanOpts(0, 0, 0, 0, B.PLAN_HOST_ONLY)
+    assert lib.plan_sparse_attn_reuse(prev.handle, m1.ctypes.data_as(C.c_void_p), C.byref(plain), 3.0, C.byref(out), None, None) == B.DBSP_ESHAPE
+    assert out.value is None
+    prev.close()
+    nxt.close()
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 128, B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY | B.PLAN_PAIR_ROWS))[0] == B.DBSP_EINVAL
+    assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 64, B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY | 4))[0] == B.DBSP_EINVAL

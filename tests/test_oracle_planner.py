@@ -425,3 +425,44 @@ def test_reward_placement_by_hand():
     for g in range(4):
         lst = r["part_items"][r["part_ptr"][g]:r["part_ptr"][g + 1]]
         assert lst == sorted(lst)
+
+
+def test_pair_rows_by_hand():
+    # one head, three query blocks (the last pair has one), five KV blocks; worked out on paper:
+    #   rows 0 and 1 need {0, 2, 3} and {2, 4}: union 0 2 3 4 -> (0, 2) with block 0 for row 0 only (flags bit 0),
+    #   block 2 for both (bits 2 and 3): 0b1101 = 13; (3, 4): 3 for row 0 (bit 0), 4 for row 1 (bit 3): 0b1001 = 9
+    #   row 2 alone needs {0, 1, 2, 3, 4}: (0, 1) and (2, 3) with bits 0 and 2: 5; (4, 4) with bit 0: 1
+    mask = np.array([[[1, 0, 1, 1, 0], [0, 0, 1, 0, 1], [1, 1, 1, 1, 1]]], dtype=np.uint8)
+    cnt, row_ptr, sbs = op.pair_rows(mask)
+    assert cnt == [2, 3] and row_ptr == [0, 2, 5]
+    assert sbs == [(0, 2, 13), (3, 4, 9), (0, 1, 5), (2, 3, 5), (4, 4, 1)]
+    pl = op.plan(mask, 2, max_item_len=-1, pair=True)
+    assert pl["nnz"] == 5 and pl["cnt"] == [2, 3]
+    assert list(pl["kv_idx"]) == [0, 2 | 13 << 24, 3, 4 | 9 << 24, 0, 1 | 5 << 24, 2, 3 | 5 << 24, 4, 4 | 1 << 24]
+    assert [tuple(i) for i in pl["items"]] == [(0, 0, 0, 2), (0, 1, 0, 3)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_pair_rows_cover_the_mask_exactly(seed):
+    # every (query block, KV block) of the mask appears in exactly one super block's flags, and nothing else does
+    rng = np.random.default_rng(seed)
+    H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 9)), int(rng.integers(1, 11))
+    mask = (rng.random((H, nQ, nK)) < rng.uniform(0.1, 0.9)).astype(np.uint8)
+    cnt, row_ptr, sbs = op.pair_rows(mask)
+    seen = np.zeros_like(mask)
+    nQ2 = (nQ + 1) // 2
+    for r in range(H * nQ2):
+        h, p = divmod(r, nQ2)
+        ids = []
+        for j0, j1, flags in sbs[row_ptr[r]:row_ptr[r + 1]]:
+            assert flags & 3, "a super block's first slot is needed by somebody"
+            for k, j in enumerate((j0, j1)):
+                for q in range(2):
+                    if flags >> (q + 2 * k) & 1:
+                        assert 2 * p + q < nQ
+                        seen[h, 2 * p + q, j] += 1
+            ids += [j0] + ([j1] if flags >> 2 else [])
+            assert (j1 > j0) if flags >> 2 else (j1 == j0)
+        assert ids == sorted(set(ids))
+        assert cnt[r] == row_ptr[r + 1] - row_ptr[r]
+    assert np.array_equal(seen, mask)
