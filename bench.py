@@ -283,6 +283,8 @@ def main():
     ap.add_argument("--no-side-measurements", action="store_true",
                     help="leave out the low-density heads and the other workload configs (extra launches after the timed region): "
                          "for profiler runs that should see the timed launches only")
+    ap.add_argument("--half-blocks", action="store_true",
+                    help="run the 64-token-block side measurement (plain kernel against pair rows) even with --no-side-measurements")
     ap.add_argument("--speedup-sweep", action="store_true",
                     help="also time the naive against the balanced placement over masks whose imbalance is dialled from 1 to 3")
     ap.add_argument("--placement-sweep", action="store_true",
@@ -501,8 +503,8 @@ def main():
         ld = low_density_heads(dbsp, torch, np, c, mask, q, k, v, o, lse, kw_timed)
         if ld is not None:
             out["low_density_heads"] = ld
-        if block == 128 and d == 128:
-            out["half_blocks_64_tokens"] = pair_rows(dbsp, synth, torch, np, c, mask, q, k, v, o, lse, kw_timed)
+    if (args.half_blocks or not args.no_side_measurements) and block == 128 and d == 128:
+        out["half_blocks_64_tokens"] = pair_rows(dbsp, synth, torch, np, c, mask, q, k, v, o, lse, kw_timed)
     if args.speedup_sweep and cfg == 3:
         out["speedup_vs_imbalance"] = speedup_sweep(dbsp, synth, torch, np, q, k, v, o, lse, kw_timed)
     if args.placement_sweep:
