@@ -103,3 +103,22 @@ def test_pair_rows_scores_that_keep_growing_take_the_rescale_path():
         plan, O, L = _run(mask, 64, qb, kb, vb, pair_rows=True, **kw)
         _check_all_rows(mask, 64, qb, kb, vb, O, L)
         plan.close()
+
+
+def test_pair_rows_through_the_entry_point_that_allocates_nothing():
+    # split pair rows put 128-row partials into the static scratch array: same results as with the plan's buffer
+    import torch
+    import paper_2511_23113_amd as dbsp
+    from test_gpu_attention import _dev
+    H, nQ, nK = 2, 5, 12
+    mask = synth.random_mask(H, nQ, nK, 0.7, seed=12, keep_diag=True)
+    qb, kb, vb = _qkv(2, H, nQ, nK, 71)
+    plan = dbsp.plan_sparse_attn(mask, 64, num_partitions=16, max_item_len=2, pair_rows=True, max_batch=2)
+    assert plan.stats(with_rho=False)["n_items"] > H * 3
+    q, k, v = _dev(qb), _dev(kb), _dev(vb)
+    o1, l1 = dbsp.sparse_attn_fwd(plan, q, k, v)
+    o2, l2 = dbsp.sparse_attn_fwd(plan, q, k, v, static_scratch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    _check_all_rows(mask, 64, qb, kb, vb, o2.float().cpu().numpy(), l2.cpu().numpy())
+    plan.close()
