@@ -171,7 +171,8 @@ int plan_sparse_attn_reuse(const dbsp_plan* previous, const uint8_t* mask_host, 
  * q:   device, bf16 [B, H, Nq, d] contiguous (d fastest);  k, v: device, bf16 [B, H, Nk, d].
  * o:   device, bf16 [B, H, Nq, d], written.  lse: device, f32 [B, H, Nq], written; may be NULL.
  *      LSE = natural log of the sum of exp(softmax_scale * q.k) over the row's active keys.
- * Nq == nQ * block and Nk == nK * block of the plan (else DBSP_ESHAPE); d in {64, 128};
+ * Nq == nQ * block and Nk == nK * block of the plan (else DBSP_ESHAPE); d in {64, 128} (128 only
+ * for a plan made with DBSP_PLAN_PAIR_ROWS, else DBSP_EINVAL);
  * the mask has no batch axis: every batch entry uses the same per-head mask.
  * softmax_scale <= 0 selects 1 / sqrt(d).  A query row with no active block gets O = 0, LSE = -inf.
  * stream: a hipStream_t (NULL = default stream).  The call only enqueues work: one persistent
@@ -190,7 +191,7 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
  * difference is where the partial results of split rows go: into a static device array of the
  * library (32 MiB per GPU, there from the moment the library is loaded until the process ends)
  * instead of the scratch the plan allocated.  It therefore works for any B whatever the plan's
- * max_batch, as long as  B * n_split_chunks * block * (d + 1) * 4 bytes (plus alignment) fit in
+ * max_batch, as long as  B * n_split_chunks * block * (d + 1) * 4 bytes (plus alignment; pair rows: 2 * block) fit in
  * the 32 MiB; beyond that it returns DBSP_EINVAL and the message names both sizes.  The call makes
  * no allocation of any kind (its first use on a device looks up the array's device address).
  * Nothing in the array needs clearing: every slot a launch reads was written by that launch.
