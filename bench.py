@@ -135,7 +135,7 @@ def pair_rows(dbsp, synth, torch, np, c, mask, q, k, v, o, lse, plan_kw, keeps=(
         flops = float(c["B"]) * nnz * 4.0 * 64 * 64 * c["d"]
         row = {"keep": keep, "active_blocks": nnz}
         for name, pair in (("plain", False), ("pair_rows", True)):
-            plan = dbsp.plan_sparse_attn(fine, 64, **dict(plan_kw, num_partitions=0, partition_cost=None, pair_rows=pair))
+            plan = dbsp.plan_sparse_attn(fine, 64, **dict(plan_kw, num_partitions=0, partition_cost=None, pair_rows=pair, head_dim=c["d"]))
             ms = timed_launches(dbsp, torch, plan, q, k, v, o, lse, reps=5, warm=3)
             rho_busy, _ = busy_rho_per_cu(np, plan)
             st = plan.stats(with_rho=False)

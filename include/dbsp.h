@@ -62,8 +62,8 @@ typedef struct dbsp_plan_opts {
   int32_t num_partitions; /* P >= 1; 0 -> number of compute units of the current device (256 when no device),
                              times 4 when block <= 64 without DBSP_PLAN_PAIR_ROWS (those workgroups are two
                              waves each: four fill a compute unit at d = 64; at d = 128 their tiles leave room
-                             for two at a time and the other half of the workgroups follow as the first finish,
-                             which the even split allows) */
+                             for two at a time: times 2 if head_dim says so, else the other half of the
+                             workgroups follow as the first finish, which costs about a tenth) */
   int32_t mode;           /* DBSP_MODE_BALANCED: greedy longest-first placement (Alg. 1, first loop);
                              DBSP_MODE_NAIVE: items in row-major order dealt in contiguous runs of
                              ceil(n_items / P) -- the unbalanced baseline rho_s is quoted against;
@@ -109,6 +109,9 @@ typedef struct dbsp_plan_opts {
                              units.  Heads come in descending order of block count, so the queue holds the lightest
                              rows.  Results do not depend on who computes an item.  0 = everything placed */
   double reward;          /* DBSP_MODE_REWARD only: R_b >= 0 (0 = plain greedy) */
+  int32_t head_dim;       /* 0, 64 or 128: the head dim the plan will run at, if known.  Only the default of
+                             num_partitions looks at it: 64-token blocks without pair rows at head dim 128 keep two
+                             workgroups per compute unit resident, so the default is twice the compute units there */
 } dbsp_plan_opts;
 
 /*

@@ -38,7 +38,8 @@ class DbspError(RuntimeError):
 class PlanOpts(C.Structure):
     _fields_ = [("num_partitions", C.c_int32), ("mode", C.c_int32), ("max_item_len", C.c_int32),
                 ("item_overhead", C.c_int32), ("flags", C.c_int32), ("locality_groups", C.c_int32),
-                ("partition_cost", C.c_void_p), ("max_batch", C.c_int32), ("dynamic_tail", C.c_int32), ("reward", C.c_double)]
+                ("partition_cost", C.c_void_p), ("max_batch", C.c_int32), ("dynamic_tail", C.c_int32), ("reward", C.c_double),
+                ("head_dim", C.c_int32)]
 
 
 _lib = None
@@ -176,7 +177,7 @@ class Plan:
 def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE_BALANCED,
                      max_item_len: int = 0, item_overhead: int = 0, host_only: bool = False,
                      locality_groups: int = 0, partition_cost=None, max_batch: int = 0, dynamic_tail: int = 0,
-                     reward: float = 0.0, pair_rows: bool = False) -> Plan:
+                     reward: float = 0.0, pair_rows: bool = False, head_dim: int = 0) -> Plan:
     """mask: uint8 host array [H, nQ, nK]; returns a Plan (see dbsp.h: plan_sparse_attn)."""
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.ndim != 3:
@@ -190,7 +191,8 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
             raise ValueError("partition_cost must hold one value per partition")
     flags = (PLAN_HOST_ONLY if host_only else 0) | (PLAN_PAIR_ROWS if pair_rows else 0)
     opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, flags, locality_groups,
-                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, float(reward))
+                    cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, float(reward),
+                    head_dim)
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
     return Plan(out.value, H, nQ, nK, block, pair_rows)

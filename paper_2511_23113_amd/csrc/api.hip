@@ -246,6 +246,8 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     return fail(DBSP_EINVAL, std::string(who) + ": dynamic_tail is a permille in [0, 1000) and goes with DBSP_MODE_ROUNDS only");
   if (!(o.reward >= 0.0) || (o.reward != 0.0 && o.mode != DBSP_MODE_REWARD) || (o.mode == DBSP_MODE_REWARD && o.partition_cost))
     return fail(DBSP_EINVAL, std::string(who) + ": reward must be >= 0, goes with DBSP_MODE_REWARD only, and that mode takes no partition_cost");
+  if (o.head_dim != 0 && o.head_dim != 64 && o.head_dim != 128)
+    return fail(DBSP_EINVAL, std::string(who) + ": head_dim is 0 (unknown), 64 or 128");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
   const bool pair = (o.flags & DBSP_PLAN_PAIR_ROWS) != 0;
   if (pair && block != 64) return fail(DBSP_EINVAL, std::string(who) + ": DBSP_PLAN_PAIR_ROWS goes with 64-token blocks");
@@ -265,7 +267,7 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     // a 64-token block is served by a two-wave workgroup: four of them fill a compute unit at d = 64
     // (at d = 128 two are resident at a time; the plan does not know d, and an even split runs in two rounds);
     // pair rows are served by eight-wave workgroups, one per compute unit
-    if (block <= 64 && !pair) P *= 4;
+    if (block <= 64 && !pair) P *= (o.head_dim == 128 ? 2 : 4);
   }
   if (previous && (previous->host.H != H || previous->host.nQ_blocks != nQ || previous->host.nK != nK || previous->host.P != P))
     return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan has a different geometry or partition count");

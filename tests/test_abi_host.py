@@ -449,3 +449,9 @@ def test_pair_rows_bit_exact_reuse_and_errors():
     m = np.ones((1, 2, 2), dtype=np.uint8)
     assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 128, B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY | B.PLAN_PAIR_ROWS))[0] == B.DBSP_EINVAL
     assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 64, B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY | 4))[0] == B.DBSP_EINVAL
+    # default partition counts without a device: 256 compute units assumed
+    for kw, want in ((dict(), 1024), (dict(head_dim=64), 1024), (dict(head_dim=128), 512), (dict(pair_rows=True, head_dim=128), 256)):
+        pl = B.plan_sparse_attn(m, 64, host_only=True, **kw)
+        assert pl.stats(with_rho=False)["num_partitions"] == want
+        pl.close()
+    assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 64, B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY, 0, None, 0, 0, 0.0, 96))[0] == B.DBSP_EINVAL
