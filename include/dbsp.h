@@ -288,7 +288,7 @@ int dbsp_ring_work(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, 
 /* Plan arrays (host copies, owned by the plan, valid until dbsp_plan_destroy). */
 enum dbsp_plan_array {
   DBSP_ROW_PTR = 0,         /* int32 [H*nQ + 1]  CSR offsets over rows r = h*nQ + I                  */
-  DBSP_KV_IDX = 1,          /* int32 [nnz]       ascending active KV block ids of each row            */
+  DBSP_KV_IDX = 1,          /* int32 [nnz]       ascending active KV block ids of each row (pair rows: [2 nnz]) */
   DBSP_ITEMS = 2,           /* int32 [n_items*4] (head, q_block, kv_begin, kv_end); begin/end are
                                positions inside the row's list                                        */
   DBSP_ITEM_SLOT = 3,       /* int32 [n_items]   -1 = whole row; else index of this chunk among all

@@ -117,7 +117,7 @@ void free_device(dbsp_device_plan& d) {
   d = dbsp_device_plan();
 }
 
-// Pinned memory for the index lists (nnz + 8 int32): the compaction writes straight into it, it is
+// Pinned memory for the index lists (the plan's kv_ints() + 8 int32): the compaction writes straight into it, it is
 // the source of the upload and the plan's host copy of the lists.
 int get_kv_staging(dbsp_plan* plan) {
   dbsp_device_plan& dv = plan->dev;

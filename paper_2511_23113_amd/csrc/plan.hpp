@@ -83,7 +83,7 @@ struct dbsp_plan {
 // Host planner (pure integer work, no HIP), in three phases so that the caller can provide the
 // destination of the index lists (pinned memory) and overlap their compaction with the placement:
 //   dbsp_plan_count      per-row counts, row offsets, per-head sums, nnz
-//   dbsp_compact_begin   starts writing the ascending KV block ids of every row to dst (nnz + 8
+//   dbsp_compact_begin   starts writing the ascending KV block ids of every row to dst (kv_ints() + 8
 //                        elements) on helper threads; dbsp_compact_end waits (true = all went well).
 //                        The mask and the plan's counts must stay untouched in between.
 //   dbsp_plan_place      work items, placement, per-partition lists, rho_s (needs the counts only)

@@ -450,7 +450,8 @@ int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ_blocks, int32_t n
   }
 }
 
-// Ascending KV block ids of every row, written to dst[row_ptr[r] ...) (dst holds nnz + 8 elements).
+// Ascending KV block ids of every row, written to dst[row_ptr[r] ...) (dst holds kv_ints() + 8 elements;
+// pair mode: two words per super block at dst[2 * row_ptr[r] ...), see compact_pair).
 // compact_row stores up to 8 elements past a row's end: harmless while that stays inside the
 // thread's own range (later rows overwrite them) or in the slack at the very end; a row whose
 // spill would reach the next thread's range goes through a bounce buffer.
