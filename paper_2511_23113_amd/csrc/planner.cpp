@@ -438,7 +438,8 @@ int dbsp_plan_count(const uint8_t* mask, int32_t H, int32_t nQ_blocks, int32_t n
     int64_t total = 0;
     for (int64_t r = 0; r < R; ++r) {
       total += hp.row_cnt[r];
-      if (total > (int64_t)INT32_MAX) { err = "more than 2^31-1 active blocks"; return DBSP_EINVAL; }
+      // offsets into the index lists are int32 (pair mode: two words per super block)
+      if (total > (int64_t)INT32_MAX / (pair ? 2 : 1)) { err = "more than 2^31-1 index-list entries"; return DBSP_EINVAL; }
       hp.row_ptr[r + 1] = (int32_t)total;
       hp.blocks_per_head[r / nQ] += hp.row_cnt[r];
     }
