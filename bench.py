@@ -144,6 +144,10 @@ def pair_rows(dbsp, synth, torch, np, c, mask, q, k, v, o, lse, plan_kw, keeps=(
             if pair:
                 row[name]["flag_fill"] = nnz / (4.0 * st["nnz"])
             plan.close()
+        auto = dbsp.plan_sparse_attn(fine, 64, **dict(plan_kw, num_partitions=0, partition_cost=None, pair_rows="auto", head_dim=c["d"],
+                                                         host_only=True))
+        row["auto_choice"] = "pair_rows" if auto.pair_rows else "plain"      # what DBSP_PLAN_PAIR_AUTO plans with
+        auto.close()
         rows.append(row)
     return rows
 

@@ -45,7 +45,7 @@ enum { DBSP_MODE_BALANCED = 0, DBSP_MODE_NAIVE = 1, DBSP_MODE_ROUNDS = 2, DBSP_M
 enum {
   DBSP_PLAN_HOST_ONLY = 1, /* flags bit: build the plan on the host only (no device, no upload);
                               such a plan cannot be passed to sparse_attn_fwd */
-  DBSP_PLAN_PAIR_ROWS = 2  /* flags bit, block == 64 only, forward pass at d == 128 only: 64-token blocks (the block
+  DBSP_PLAN_PAIR_ROWS = 2, /* flags bit, block == 64 only, forward pass at d == 128 only: 64-token blocks (the block
                               size of the paper's PAROAttention masks: Methodology, "Block-level Partitioning") served
                               by 128-query workgroups.  A row of the plan is then a pair of neighbouring query blocks
                               (2p, 2p+1) of a head and its KV list the ascending union of the two rows' lists, cut into
@@ -54,10 +54,15 @@ enum {
                               mask does not have are computed with the rest and given probability zero, so K and V
                               must be finite in every block that either row of a pair uses.  It pays when neighbouring
                               rows are alike: from about 0.65 of the flags set (the mask's active blocks / (4 x the
-                              plan's nnz)) it is faster than the plain plan, up to 1.5 times.  DBSP_ROW_CNT / ROW_PTR / ITEMS then refer to pair rows (ceil(nQ / 2) per head) and
-                              super blocks, and DBSP_KV_IDX holds two int32 per super block: j0, and j1 | flags << 24
+                              plan's nnz)) it is faster than the plain plan, up to 1.5 times.  DBSP_ROW_CNT /
+                              ROW_PTR / ITEMS then refer to pair rows (ceil(nQ / 2) per head) and super blocks,
+                              and DBSP_KV_IDX holds two int32 per super block: j0, and j1 | flags << 24
                               with flags bit (q + 2k) = "query block 2p+q needs KV block j_k" (a union of odd length
                               ends with j1 = j0 and no flag for the second slot) */
+  DBSP_PLAN_PAIR_AUTO = 4  /* flags bit, block == 64 and head_dim == 128 only, not together with DBSP_PLAN_PAIR_ROWS:
+                              the library counts the mask both ways and plans with pair rows if at least 0.65 of the
+                              flags would be set (5 x active blocks >= 13 x super blocks), else plainly;
+                              dbsp_plan_pair_rows tells which.  plan_sparse_attn_reuse keeps the previous plan's kind */
 };
 
 typedef struct dbsp_plan_opts {
@@ -86,7 +91,7 @@ typedef struct dbsp_plan_opts {
                              ceil(cnt / max_item_len) near-equal chunks. 0 -> max(4, nnz / (2 P)); < 0 -> never split */
   int32_t item_overhead;  /* >= 0; constant added to every item's weight for the greedy placement only
                              (rho_s is always computed from pure block counts). 0 = the paper's cost model */
-  int32_t flags;          /* DBSP_PLAN_HOST_ONLY | DBSP_PLAN_PAIR_ROWS, or 0 */
+  int32_t flags;          /* DBSP_PLAN_HOST_ONLY, DBSP_PLAN_PAIR_ROWS or DBSP_PLAN_PAIR_AUTO, or'ed; or 0 */
   int32_t locality_groups; /* DBSP_MODE_ROUNDS only: G > 1 keeps runs of neighbouring query blocks inside one
                              group of partitions that share a cache (partition p belongs to group p mod G;
                              on MI355X workgroup p runs on XCD p mod 8, each XCD has its own L2).  A round is
@@ -144,6 +149,10 @@ typedef struct dbsp_plan_opts {
  */
 int plan_sparse_attn(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK, int32_t block,
                      const dbsp_plan_opts* opts, dbsp_plan** out_plan);
+
+/* Whether the plan was made with pair rows (DBSP_PLAN_PAIR_ROWS, or DBSP_PLAN_PAIR_AUTO's choice): 1 or 0.
+ * Errors: DBSP_EINVAL (null pointer). */
+int dbsp_plan_pair_rows(const dbsp_plan* plan, int32_t* pair_rows);
 
 /*
  * plan_sparse_attn_reuse -- plan for the next mask of a sequence (denoising steps), keeping the

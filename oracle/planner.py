@@ -94,6 +94,14 @@ def pair_rows(mask):
     return cnt, row_ptr, sbs
 
 
+def pair_rows_pay(mask) -> bool:
+    """The library's rule for choosing pair rows by itself: at least 0.65 of the (query block, KV block)
+    combinations of the super blocks are the mask's own, i.e. active blocks / (4 * super blocks) >= 13 / 20
+    (the measured break-even against the plain plan), taken in integers."""
+    cnt, _, _ = pair_rows(mask)
+    return 5 * int((np.asarray(mask) != 0).sum()) >= 13 * sum(cnt)
+
+
 def auto_max_item_len(total_blocks: int, P: int) -> int:
     """Split threshold when the caller gives none: max(4, total // (2 P)).
 
@@ -346,9 +354,12 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
     reward (MODE_REWARD only): the paper's R_b, see reward_partition.
     pair: rows are the super-rows of pair_rows (two query blocks each) and the unit of work is the
     super block; nQ, cnt, row_ptr, items, nnz are then in those units and kv_idx holds, per super
-    block, j0 and j1 | flags << 24."""
+    block, j0 and j1 | flags << 24.  pair = "auto": decided by pair_rows_pay (a chain of plans keeps the
+    first one's choice); the result's "pair" says which."""
     mask = np.asarray(mask)
     H, nQ, nK = mask.shape
+    if pair == "auto":
+        pair = previous["pair"] if previous is not None else pair_rows_pay(mask)
     if pair:
         cnt, row_ptr, sbs = pair_rows(mask)
         nQ = (nQ + 1) // 2
@@ -414,7 +425,7 @@ def plan(mask, P: int, mode: int = MODE_BALANCED, max_item_len: int = 0, item_ov
         part_ptr=part_ptr, part_items=part_items, tail_items=tail_items,
         part_load=loads_of(assign),
         rho_naive=rho_naive, rho_balanced=rho_bal, rho_plan=imbalance_ratio([loads_of(assign)]),
-        reused=reused, rho_reuse=rho_reuse,
+        reused=reused, rho_reuse=rho_reuse, pair=bool(pair),
     )
 
 

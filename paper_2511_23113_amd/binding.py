@@ -18,13 +18,14 @@ DBSP_OK, DBSP_EINVAL, DBSP_ESHAPE, DBSP_ENOMEM, DBSP_EHIP = 0, -1, -2, -3, -4
 MODE_BALANCED, MODE_NAIVE, MODE_ROUNDS, MODE_REWARD = 0, 1, 2, 3
 PLAN_HOST_ONLY = 1
 PLAN_PAIR_ROWS = 2
+PLAN_PAIR_AUTO = 4
 
 ROW_PTR, KV_IDX, ITEMS, ITEM_SLOT, SPLIT_ROWS, PART_PTR, PART_ITEMS, PART_LOAD, BLOCKS_PER_HEAD, ROW_CNT, EMPTY_ROWS, TAIL_ITEMS = range(12)
 _INT64_ARRAYS = (PART_LOAD, BLOCKS_PER_HEAD)
 
 EXPORTS = (
     "plan_sparse_attn", "plan_sparse_attn_reuse", "sparse_attn_fwd", "sparse_attn_fwd_static", "imbalance_ratio", "dbsp_plan_get", "dbsp_plan_stats",
-    "dbsp_plan_busy", "dbsp_plan_tail_takes", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
+    "dbsp_plan_busy", "dbsp_plan_tail_takes", "dbsp_plan_pair_rows", "dbsp_plan_calibrate", "dbsp_plan_destroy", "dbsp_last_error",
     "dbsp_partition_heads", "dbsp_partition_blocks", "dbsp_ring_work", "dbsp_fit_cost_model", "dbsp_mfma_probe",
 )
 
@@ -88,6 +89,8 @@ def load_library(path: str | None = None):
     lib.dbsp_plan_busy.restype = C.c_int
     lib.dbsp_plan_tail_takes.argtypes = [vp, vp, vp]
     lib.dbsp_plan_tail_takes.restype = C.c_int
+    lib.dbsp_plan_pair_rows.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.dbsp_plan_pair_rows.restype = C.c_int
     lib.dbsp_plan_destroy.argtypes = [vp]
     lib.dbsp_plan_destroy.restype = None
     lib.dbsp_last_error.argtypes = []
@@ -189,13 +192,17 @@ def plan_sparse_attn(mask, block: int, num_partitions: int = 0, mode: int = MODE
             num_partitions = int(cost.shape[0])      # one cost per partition: the array fixes their number
         if cost.ndim != 1 or cost.shape[0] != num_partitions:
             raise ValueError("partition_cost must hold one value per partition")
-    flags = (PLAN_HOST_ONLY if host_only else 0) | (PLAN_PAIR_ROWS if pair_rows else 0)
+    if pair_rows not in (False, True, "auto"):
+        raise ValueError('pair_rows is False, True or "auto"')
+    flags = (PLAN_HOST_ONLY if host_only else 0) | (PLAN_PAIR_AUTO if pair_rows == "auto" else PLAN_PAIR_ROWS if pair_rows else 0)
     opts = PlanOpts(num_partitions, mode, max_item_len, item_overhead, flags, locality_groups,
                     cost.ctypes.data_as(C.c_void_p) if cost is not None else None, max_batch, dynamic_tail, float(reward),
                     head_dim)
     out = C.c_void_p()
     _check(load_library().plan_sparse_attn(mask.ctypes.data_as(C.c_void_p), H, nQ, nK, block, C.byref(opts), C.byref(out)))
-    return Plan(out.value, H, nQ, nK, block, pair_rows)
+    chosen = C.c_int32()
+    _check(load_library().dbsp_plan_pair_rows(out, C.byref(chosen)))
+    return Plan(out.value, H, nQ, nK, block, bool(chosen.value))
 
 
 def plan_sparse_attn_reuse(previous: Plan, mask, reuse_threshold: float, num_partitions: int = 0, mode: int = MODE_BALANCED,

@@ -240,7 +240,7 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   if (opts) o = *opts;
   if (o.num_partitions < 0 || o.item_overhead < 0 ||
       (o.mode != DBSP_MODE_BALANCED && o.mode != DBSP_MODE_NAIVE && o.mode != DBSP_MODE_ROUNDS && o.mode != DBSP_MODE_REWARD) ||
-      (o.flags & ~(DBSP_PLAN_HOST_ONLY | DBSP_PLAN_PAIR_ROWS)) || o.locality_groups < 0 || o.max_batch < 0)
+      (o.flags & ~(DBSP_PLAN_HOST_ONLY | DBSP_PLAN_PAIR_ROWS | DBSP_PLAN_PAIR_AUTO)) || o.locality_groups < 0 || o.max_batch < 0)
     return fail(DBSP_EINVAL, std::string(who) + ": bad option (partitions < 0, overhead < 0, groups < 0, max_batch < 0, unknown mode or flag)");
   if (o.dynamic_tail < 0 || o.dynamic_tail >= 1000 || (o.dynamic_tail > 0 && o.mode != DBSP_MODE_ROUNDS))
     return fail(DBSP_EINVAL, std::string(who) + ": dynamic_tail is a permille in [0, 1000) and goes with DBSP_MODE_ROUNDS only");
@@ -249,8 +249,30 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   if (o.head_dim != 0 && o.head_dim != 64 && o.head_dim != 128)
     return fail(DBSP_EINVAL, std::string(who) + ": head_dim is 0 (unknown), 64 or 128");
   const bool host_only = (o.flags & DBSP_PLAN_HOST_ONLY) != 0;
-  const bool pair = (o.flags & DBSP_PLAN_PAIR_ROWS) != 0;
-  if (pair && block != 64) return fail(DBSP_EINVAL, std::string(who) + ": DBSP_PLAN_PAIR_ROWS goes with 64-token blocks");
+  bool pair = (o.flags & DBSP_PLAN_PAIR_ROWS) != 0;
+  const bool pair_auto = (o.flags & DBSP_PLAN_PAIR_AUTO) != 0;
+  if (pair && pair_auto) return fail(DBSP_EINVAL, std::string(who) + ": DBSP_PLAN_PAIR_ROWS and DBSP_PLAN_PAIR_AUTO exclude each other");
+  if ((pair || pair_auto) && block != 64) return fail(DBSP_EINVAL, std::string(who) + ": pair rows go with 64-token blocks");
+  if (pair_auto && o.head_dim != 128) return fail(DBSP_EINVAL, std::string(who) + ": DBSP_PLAN_PAIR_AUTO needs head_dim = 128 (pair rows run at that head dim only)");
+  // DBSP_PLAN_PAIR_AUTO: a chain of plans keeps the first one's choice (items of the two kinds do not
+  // match each other); else both counts are taken and pair rows chosen from a flag fill of 0.65
+  // (5 x the mask's active blocks >= 13 x the super blocks), the measured break-even
+  dbsp_host_plan counted;
+  bool have_counts = false;
+  if (pair_auto) {
+    if (previous) {
+      pair = previous->host.pair;
+    } else {
+      std::string cerr;
+      dbsp_host_plan plain;
+      int rc = dbsp_plan_count(mask_host, H, nQ, nK, block, true, counted, cerr);
+      if (rc == DBSP_OK) rc = dbsp_plan_count(mask_host, H, nQ, nK, block, false, plain, cerr);
+      if (rc != DBSP_OK) return fail(rc, std::string(who) + ": " + cerr);
+      pair = 5 * plain.nnz >= 13 * counted.nnz;
+      if (!pair) counted = std::move(plain);
+      have_counts = true;
+    }
+  }
   if (previous && previous->host.pair != pair) return fail(DBSP_ESHAPE, std::string(who) + ": the previous plan differs in DBSP_PLAN_PAIR_ROWS");
   int32_t P = o.num_partitions;
   if (P == 0 && previous) P = previous->host.P;
@@ -294,7 +316,9 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
     // this thread builds the items and the placement; then everything is sent to the device
     dbsp_host_plan& hp = plan->host;
     plan->dev.max_batch = o.max_batch > 0 ? o.max_batch : 1;
-    int rc = dbsp_plan_count(mask_host, H, nQ, nK, block, pair, hp, err);
+    int rc = DBSP_OK;
+    if (have_counts) hp = std::move(counted);
+    else rc = dbsp_plan_count(mask_host, H, nQ, nK, block, pair, hp, err);
     if (rc != DBSP_OK) {
       delete plan;
       return fail(rc, std::string(who) + ": " + err);
@@ -325,6 +349,12 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   }
   plan->plan_usec = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t_start).count();
   *out_plan = plan;
+  return DBSP_OK;
+}
+
+int dbsp_plan_pair_rows(const dbsp_plan* plan, int32_t* pair_rows) {
+  if (!plan || !pair_rows) return fail(DBSP_EINVAL, "dbsp_plan_pair_rows: null pointer");
+  *pair_rows = plan->host.pair ? 1 : 0;
   return DBSP_OK;
 }
 

@@ -455,3 +455,35 @@ def test_pair_rows_bit_exact_reuse_and_errors():
         assert pl.stats(with_rho=False)["num_partitions"] == want
         pl.close()
     assert _plan_raw(m.ctypes.data_as(C.c_void_p), 1, 2, 2, 64, B.PlanOpts(4, 0, 0, 0, B.PLAN_HOST_ONLY, 0, None, 0, 0, 0.0, 96))[0] == B.DBSP_EINVAL
+
+
+def test_pair_auto_chooses_like_the_oracle_and_errors():
+    rng = np.random.default_rng(9)
+    seen = set()
+    for seed in range(16):
+        H, nQ, nK = int(rng.integers(1, 4)), int(rng.integers(1, 10)), int(rng.integers(2, 24))
+        base = synth.random_mask(H, (nQ + 1) // 2, nK, float(rng.uniform(0.2, 0.9)), seed=seed)
+        # neighbouring rows alike to a varying degree: copies of one row with a share of the blocks dropped
+        mask = np.repeat(base, 2, axis=1)[:, :nQ].copy()
+        mask &= (rng.random(mask.shape) < float(rng.choice([1.0, 0.9, 0.6, 0.3]))).astype(np.uint8)
+        pl = B.plan_sparse_attn(mask, 64, num_partitions=4, host_only=True, pair_rows="auto", head_dim=128)
+        ref = op.plan(mask, 4, pair="auto")
+        assert pl.pair_rows is ref["pair"]
+        seen.add(pl.pair_rows)
+        assert pl.array(B.KV_IDX).tolist() == list(ref["kv_idx"]) and pl.array(B.PART_ITEMS).tolist() == list(ref["part_items"])
+        # a chain keeps the first plan's kind whatever the next mask looks like
+        nxt, reused, rho = B.plan_sparse_attn_reuse(pl, 1 - mask, 1.0, host_only=True)
+        assert nxt.pair_rows is pl.pair_rows
+        pl.close()
+        nxt.close()
+    assert seen == {False, True}
+    m = np.ones((1, 2, 2), dtype=np.uint8)
+    mp = m.ctypes.data_as(C.c_void_p)
+    host = B.PLAN_HOST_ONLY
+    bad = (B.PlanOpts(4, 0, 0, 0, host | B.PLAN_PAIR_AUTO, 0, None, 0, 0, 0.0, 0),                      # head dim unknown
+           B.PlanOpts(4, 0, 0, 0, host | B.PLAN_PAIR_AUTO, 0, None, 0, 0, 0.0, 64),
+           B.PlanOpts(4, 0, 0, 0, host | B.PLAN_PAIR_AUTO | B.PLAN_PAIR_ROWS, 0, None, 0, 0, 0.0, 128))
+    for o in bad:
+        assert _plan_raw(mp, 1, 2, 2, 64, o)[0] == B.DBSP_EINVAL
+    assert _plan_raw(mp, 1, 2, 2, 128, B.PlanOpts(4, 0, 0, 0, host | B.PLAN_PAIR_AUTO, 0, None, 0, 0, 0.0, 128))[0] == B.DBSP_EINVAL
+    assert B.load_library().dbsp_plan_pair_rows(None, None) == B.DBSP_EINVAL

@@ -122,3 +122,19 @@ def test_pair_rows_through_the_entry_point_that_allocates_nothing():
     assert torch.equal(o1, o2) and torch.equal(l1, l2)
     _check_all_rows(mask, 64, qb, kb, vb, o2.float().cpu().numpy(), l2.cpu().numpy())
     plan.close()
+
+
+def test_pair_auto_picks_a_kind_and_both_kinds_agree_with_the_oracle():
+    # neighbouring rows alike -> pair rows; unrelated rows -> the plain plan; the results do not depend on the choice
+    import paper_2511_23113_amd as dbsp
+    H, nQ, nK = 2, 6, 16
+    alike = np.repeat(synth.random_mask(H, nQ // 2, nK, 0.5, seed=3, keep_diag=False), 2, axis=1)
+    unrelated = synth.random_mask(H, nQ, nK, 0.2, seed=4, keep_diag=False)
+    qb, kb, vb = _qkv(1, H, nQ, nK, 81)
+    for mask, want in ((alike, True), (unrelated, False)):
+        plan, O, L = _run(mask, 64, qb, kb, vb, pair_rows="auto", head_dim=128, num_partitions=8)
+        assert plan.pair_rows is want
+        _check_all_rows(mask, 64, qb, kb, vb, O, L)
+        plan.close()
+    with pytest.raises(dbsp.DbspError):
+        dbsp.plan_sparse_attn(alike, 64, pair_rows="auto")           # the head dim must be stated

@@ -466,3 +466,19 @@ def test_pair_rows_cover_the_mask_exactly(seed):
         assert ids == sorted(set(ids))
         assert cnt[r] == row_ptr[r + 1] - row_ptr[r]
     assert np.array_equal(seen, mask)
+
+
+def test_pair_rows_pay_threshold_by_hand():
+    # one pair row; row 0 needs KV blocks 0..9 (union of 10 = 5 super blocks), row 1 needs k of them:
+    # active blocks 10 + k against 4 * 5 = 20 combinations; the rule asks for 13 / 20
+    for k, want in ((10, True), (4, True), (3, True), (2, False), (0, False)):
+        mask = np.zeros((1, 2, 10), dtype=np.uint8)
+        mask[0, 0, :] = 1
+        mask[0, 1, :k] = 1
+        assert op.pair_rows_pay(mask) is want, k
+        assert op.plan(mask, 2, pair="auto")["pair"] is want
+    # disjoint rows: every super block is half used at best
+    mask = np.zeros((1, 2, 8), dtype=np.uint8)
+    mask[0, 0, :4] = 1
+    mask[0, 1, 4:] = 1
+    assert not op.pair_rows_pay(mask)
