@@ -53,15 +53,15 @@ enum {
                               of such a plan); the (query block, KV block) combinations of a super block that the
                               mask does not have are computed with the rest and given probability zero, so K and V
                               must be finite in every block that either row of a pair uses.  It pays when neighbouring
-                              rows are alike: from about 0.65 of the flags set (the mask's active blocks / (4 x the
-                              plan's nnz)) it is faster than the plain plan, up to 1.5 times.  DBSP_ROW_CNT /
+                              rows are alike: from about 5 / 8 of the flags set (the mask's active blocks / (4 x the
+                              plan's nnz)) it is faster than the plain plan, up to 1.57 times.  DBSP_ROW_CNT /
                               ROW_PTR / ITEMS then refer to pair rows (ceil(nQ / 2) per head) and super blocks,
                               and DBSP_KV_IDX holds two int32 per super block: j0, and j1 | flags << 24
                               with flags bit (q + 2k) = "query block 2p+q needs KV block j_k" (a union of odd length
                               ends with j1 = j0 and no flag for the second slot) */
   DBSP_PLAN_PAIR_AUTO = 4  /* flags bit, block == 64 and head_dim == 128 only, not together with DBSP_PLAN_PAIR_ROWS:
-                              the library counts the mask both ways and plans with pair rows if at least 0.65 of the
-                              flags would be set (5 x active blocks >= 13 x super blocks), else plainly;
+                              the library counts the mask both ways and plans with pair rows if at least 5 / 8 of the
+                              flags would be set (2 x active blocks >= 5 x super blocks), else plainly;
                               dbsp_plan_pair_rows tells which.  plan_sparse_attn_reuse keeps the previous plan's kind */
 };
 

@@ -95,11 +95,11 @@ def pair_rows(mask):
 
 
 def pair_rows_pay(mask) -> bool:
-    """The library's rule for choosing pair rows by itself: at least 0.65 of the (query block, KV block)
-    combinations of the super blocks are the mask's own, i.e. active blocks / (4 * super blocks) >= 13 / 20
+    """The library's rule for choosing pair rows by itself: at least 5 / 8 of the (query block, KV block)
+    combinations of the super blocks are the mask's own, i.e. active blocks / (4 * super blocks) >= 5 / 8
     (the measured break-even against the plain plan), taken in integers."""
     cnt, _, _ = pair_rows(mask)
-    return 5 * int((np.asarray(mask) != 0).sum()) >= 13 * sum(cnt)
+    return 2 * int((np.asarray(mask) != 0).sum()) >= 5 * sum(cnt)
 
 
 def auto_max_item_len(total_blocks: int, P: int) -> int:

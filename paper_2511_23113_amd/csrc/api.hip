@@ -255,8 +255,8 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
   if ((pair || pair_auto) && block != 64) return fail(DBSP_EINVAL, std::string(who) + ": pair rows go with 64-token blocks");
   if (pair_auto && o.head_dim != 128) return fail(DBSP_EINVAL, std::string(who) + ": DBSP_PLAN_PAIR_AUTO needs head_dim = 128 (pair rows run at that head dim only)");
   // DBSP_PLAN_PAIR_AUTO: a chain of plans keeps the first one's choice (items of the two kinds do not
-  // match each other); else both counts are taken and pair rows chosen from a flag fill of 0.65
-  // (5 x the mask's active blocks >= 13 x the super blocks), the measured break-even
+  // match each other); else both counts are taken and pair rows chosen from a flag fill of 5 / 8
+  // (2 x the mask's active blocks >= 5 x the super blocks), the measured break-even
   dbsp_host_plan counted;
   bool have_counts = false;
   if (pair_auto) {
@@ -268,7 +268,7 @@ static int make_plan(const uint8_t* mask_host, int32_t H, int32_t nQ, int32_t nK
       int rc = dbsp_plan_count(mask_host, H, nQ, nK, block, true, counted, cerr);
       if (rc == DBSP_OK) rc = dbsp_plan_count(mask_host, H, nQ, nK, block, false, plain, cerr);
       if (rc != DBSP_OK) return fail(rc, std::string(who) + ": " + cerr);
-      pair = 5 * plain.nnz >= 13 * counted.nnz;
+      pair = 2 * plain.nnz >= 5 * counted.nnz;
       if (!pair) counted = std::move(plain);
       have_counts = true;
     }

@@ -500,6 +500,7 @@ void dbsp_fwd_kernel(
 
         // ---- first half: MFMAs on the operands read during the previous step; reads for the second half
         int jk = 0;
+        [[maybe_unused]] int kw0 = 0, kw1 = 0;
 #pragma unroll
         for (int x = 0; x < SLOTS; ++x) {
           if constexpr (QK) kaB[x] = read_k(bq, HALF, KH + x);
@@ -512,10 +513,12 @@ void dbsp_fwd_kernel(
           }
           if constexpr (BAR) {
             // id of the block whose K is copied after the barrier below, through the scalar cache
-            // (pair mode: and this wave's flag of that block)
+            // (pair mode: the two words of that super block; they are taken apart behind the
+            // barrier, whose wait covers the loads, so that nothing here waits for them)
             if (x == SLOTS - 1) {
-              jk = block_of((Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1);
-              if constexpr (PAIR) a_next2 = (Tq + 2 < n_tiles) && active_in(Tq + 2);
+              const int Tn = (Tq + 2 < n_tiles) ? Tq + 2 : n_tiles - 1;
+              if constexpr (PAIR) { kw0 = kv[2 * Tn]; kw1 = kv[2 * Tn + 1]; }
+              else jk = kv[Tn];
             }
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -530,6 +533,10 @@ void dbsp_fwd_kernel(
           }
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           __syncthreads();
+          if constexpr (PAIR) {
+            jk = (w < C::NW / 2) ? kw0 : (kw1 & 0xffffff);
+            a_next2 = (Tq + 2 < n_tiles) && ((kw1 >> flag_bit) & 1) != 0;
+          }
           if (Tq + 2 < n_tiles) copy_k_tile(jk, bq);
           if (Tq + 1 < n_tiles) copy_v_tile(j_v, 1 - bq);
           j_v = jk;

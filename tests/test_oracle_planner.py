@@ -470,7 +470,7 @@ def test_pair_rows_cover_the_mask_exactly(seed):
 
 def test_pair_rows_pay_threshold_by_hand():
     # one pair row; row 0 needs KV blocks 0..9 (union of 10 = 5 super blocks), row 1 needs k of them:
-    # active blocks 10 + k against 4 * 5 = 20 combinations; the rule asks for 13 / 20
+    # active blocks 10 + k against 4 * 5 = 20 combinations; the rule asks for 5 / 8 of them, that is 12.5
     for k, want in ((10, True), (4, True), (3, True), (2, False), (0, False)):
         mask = np.zeros((1, 2, 10), dtype=np.uint8)
         mask[0, 0, :] = 1
