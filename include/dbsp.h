@@ -205,8 +205,8 @@ int sparse_attn_fwd(const dbsp_plan* plan, const void* q, const void* k, const v
  * difference is where the partial results of split rows go: into a static device array of the
  * library (32 MiB per GPU, there from the moment the library is loaded until the process ends)
  * instead of the scratch the plan allocated.  It therefore works for any B whatever the plan's
- * max_batch, as long as  B * n_split_chunks * block * (d + 1) * 4 bytes (plus alignment; pair rows: 2 * block) fit in
- * the 32 MiB; beyond that it returns DBSP_EINVAL and the message names both sizes.  The call makes
+ * max_batch, as long as  B * n_split_chunks * block * (d + 1) * 4 bytes (plus alignment; with pair
+ * rows 2 * block in place of block) fit in the 32 MiB; beyond that it returns DBSP_EINVAL and the message names both sizes.  The call makes
  * no allocation of any kind (its first use on a device looks up the array's device address).
  * Nothing in the array needs clearing: every slot a launch reads was written by that launch.
  * All calls on one GPU share the array: two such calls must not overlap on the device (different
